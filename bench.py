@@ -1,0 +1,180 @@
+#!/usr/bin/env python3
+"""Benchmark of the Tier-2 attention step on one MI355X.
+
+A step is one pass of the whole hot path over one batch of synthetic input already resident
+in HBM: gh_kv_append -> gh_decode_attention -> gh_decode_reduce on one stream.  The same row is
+re-appended at the same position every step, so each step moves identical bytes.
+
+Prints ONE JSON line on stdout (diagnostics go to stderr):
+  value     sequence-steps per second over the timed steps (wall clock, sync on both sides)
+  roofline  the attention kernel's algorithmic bytes per launch / its mean duration between HIP
+            events on the launch stream, against the 8 TB/s HBM peak
+  cpu_baseline  the float64 oracle timed on the host cores on a bounded sample of the same workload
+"""
+import argparse
+import json
+import os
+import sys
+import time
+
+ROOT = os.path.dirname(os.path.abspath(__file__))
+if ROOT not in sys.path:
+    sys.path.insert(0, ROOT)
+
+HBM_PEAK_GBS = 8000.0   # MI355X published HBM3E peak
+
+CONFIG_OF = {"c1": "configs[0]", "c2": "configs[1]", "c3": "configs[2]", "c4": "configs[3]",
+             "c5": "configs[4]"}
+
+
+def log(*a):
+    print(*a, file=sys.stderr, flush=True)
+
+
+def cpu_baseline(inp, target_s=12.0):
+    """Time the oracle (append + attention) on the first S sequences of the workload."""
+    import numpy as np
+    import torch
+    from oracle import gh_oracle as O
+    from paper_2501_11779_amd import workloads as W
+
+    w = inp["workload"]
+    B = w.batch
+
+    def run(S):
+        slots = torch.from_numpy(inp["slots"][:S].astype(np.int64)).to(inp["k_cache"].device)
+        kc = W.bits(inp["k_cache"].index_select(0, slots))
+        vc = W.bits(inp["v_cache"].index_select(0, slots))
+        q, kn, vn = W.bits(inp["q"][:S]), W.bits(inp["k_new"][:S]), W.bits(inp["v_new"][:S])
+        strides = W.cache_shape_and_strides(S, w.n_kv_heads, inp["capacity"], w.head_dim,
+                                            inp["layout"])[1]
+        p = O.make_problem(S, w.n_q_heads, w.n_kv_heads, w.head_dim, W.DTYPE_CODE[w.dtype], S,
+                           inp["capacity"], inp["scale"], strides)
+        sid = np.arange(S, dtype=np.int32)
+        pos = inp["lengths"][:S].astype(np.int32)
+        t0 = time.perf_counter()
+        O.kv_append(p, kc, vc, kn, vn, sid, pos)
+        O.decode_attention(p, q, kc, vc, sid, pos + 1)
+        return time.perf_counter() - t0
+
+    S0 = min(B, 2)
+    t_probe = run(S0)
+    S = int(max(S0, min(B, round(S0 * target_s / max(t_probe, 1e-6)))))
+    S = min(S, 512)
+    t = run(S)
+    return {"value": S / t, "unit": "sequence-steps/s", "cores": O.num_threads(), "kind": "oracle",
+            "sample": f"first {S} of {B} sequences of the same workload (float64 append + attention, "
+                      f"{t:.2f} s)"}
+
+
+def main():
+    ap = argparse.ArgumentParser()
+    ap.add_argument("--gpus", type=int, default=1)
+    ap.add_argument("--steps", type=int, default=50)
+    ap.add_argument("--warmup", type=int, default=10)
+    ap.add_argument("--workload", default="c4", choices=sorted(CONFIG_OF))
+    ap.add_argument("--kernel", default="auto", choices=["auto", "valu", "mfma"])
+    ap.add_argument("--chunk-rows", type=int, default=0)
+    ap.add_argument("--no-cpu-baseline", action="store_true")
+    ap.add_argument("--traffic-bytes", type=float, default=None,
+                    help="HBM bytes per attention launch from rocprofv3 counters, if measured")
+    args = ap.parse_args()
+    if args.gpus != 1:
+        sys.exit("bench.py: this build runs on one GPU only (the path shards by sequence with no "
+                 "exchange step; see DESIGN.md); run with --gpus 1")
+
+    import numpy as np
+    import torch
+    from paper_2501_11779_amd import binding as G
+    from paper_2501_11779_amd import workloads as W
+
+    assert torch.cuda.is_available(), "bench.py needs a GPU"
+    torch.cuda.set_device(0)
+    G.lib()
+    props = torch.cuda.get_device_properties(0)
+    log(f"device: {props.name} CUs={props.multi_processor_count} "
+        f"mem={props.total_memory / 2**30:.0f} GiB host_cpus={os.cpu_count()}")
+
+    w = W.WORKLOADS[args.workload]
+    t0 = time.perf_counter()
+    inp = W.make_inputs(w, "cuda")
+    torch.cuda.synchronize()
+    kernel = {"auto": G.GH_KERNEL_AUTO, "valu": G.GH_KERNEL_VALU, "mfma": G.GH_KERNEL_MFMA}[args.kernel]
+    p = G.problem_from_inputs(inp, chunk_rows=args.chunk_rows, kernel=kernel)
+    ws = G.alloc_workspace(p)
+    out = torch.empty((w.batch, w.n_q_heads, w.head_dim), dtype=torch.float32, device="cuda")
+    ctx = inp["lengths"].astype(np.int64) + 1
+    step_bytes = W.algorithmic_bytes(w, ctx)
+    attn_bytes = W.attention_bytes(w, ctx)
+    flops = W.algorithmic_flops(w, ctx)
+    chunk_rows, n_chunks = G.gh_decode_chunk_rows(p), G.gh_decode_num_chunks(p)
+    log(f"workload {w.name}: B={w.batch} H={w.n_q_heads}/{w.n_kv_heads} d={w.head_dim} {w.dtype} "
+        f"sum(n_b)={int(ctx.sum())} step_bytes={step_bytes / 1e9:.3f} GB "
+        f"attn_bytes={attn_bytes / 1e9:.3f} GB chunk_rows={chunk_rows} n_chunks={n_chunks} "
+        f"workspace={ws.numel() * 4 / 1e6:.1f} MB setup={time.perf_counter() - t0:.1f} s")
+
+    def step(events=None):
+        G.check(G.gh_kv_append(p, inp["k_cache"], inp["v_cache"], inp["k_new"], inp["v_new"],
+                               inp["slot_id"], inp["pos"], None))
+        if events is not None:
+            events[0].record()
+        G.check(G.gh_decode_attention(p, inp["q"], inp["k_cache"], inp["v_cache"], inp["slot_id"],
+                                      inp["ctx_len"], ws))
+        if events is not None:
+            events[1].record()
+        G.check(G.gh_decode_reduce(p, ws, inp["ctx_len"], out))
+        if events is not None:
+            events[2].record()
+
+    for _ in range(args.warmup):
+        step()
+    torch.cuda.synchronize()
+    evs = [[torch.cuda.Event(enable_timing=True) for _ in range(3)] for _ in range(args.steps)]
+    torch.cuda.synchronize()
+    t0 = time.perf_counter()
+    for i in range(args.steps):
+        step(evs[i])
+    torch.cuda.synchronize()
+    elapsed = time.perf_counter() - t0
+
+    attn_ms = np.array([e[0].elapsed_time(e[1]) for e in evs])
+    red_ms = np.array([e[1].elapsed_time(e[2]) for e in evs])
+    ms_per_step = elapsed / args.steps * 1e3
+    attn_avg_s = float(attn_ms.mean()) * 1e-3
+    achieved = attn_bytes / attn_avg_s / 1e9
+    log(f"step {ms_per_step:.4f} ms | attention mean {attn_ms.mean():.4f} ms median "
+        f"{np.median(attn_ms):.4f} min {attn_ms.min():.4f} | reduce mean {red_ms.mean():.4f} ms | "
+        f"attention {achieved:.0f} GB/s = {achieved / HBM_PEAK_GBS * 100:.1f}% of {HBM_PEAK_GBS:.0f} | "
+        f"whole step {step_bytes / (elapsed / args.steps) / 1e9:.0f} GB/s | "
+        f"{flops / attn_avg_s / 1e12:.1f} TFLOP/s algorithmic")
+
+    result = {
+        "metric": "decode-attention sequence-steps/sec (achieved HBM GB/s and % of peak under roofline)",
+        "value": w.batch * args.steps / elapsed,
+        "unit": "sequence-steps/s",
+        "n_gpus": 1, "steps": args.steps, "warmup": args.warmup,
+        "ms_per_step": ms_per_step,
+        "higher_is_better": True, "scaling": "weak", "vs_baseline": None,
+        "dtype": w.dtype, "data": "synthetic",
+        "config": {"workload": f"{CONFIG_OF[w.name]} ({w.note}): B={w.batch}, H={w.n_q_heads}, "
+                               f"H_kv={w.n_kv_heads}, d={w.head_dim}, lengths={list(w.lengths)}, "
+                               f"seed={w.seed}",
+                   "kernel": args.kernel, "chunk_rows": chunk_rows, "n_chunks": n_chunks,
+                   "step": "gh_kv_append + gh_decode_attention + gh_decode_reduce",
+                   "step_algorithmic_bytes": step_bytes,
+                   "step_GBps": step_bytes / (elapsed / args.steps) / 1e9},
+        "roofline": {"bound": "hbm", "kernel": "gh_decode_attention",
+                     "achieved": achieved, "peak": HBM_PEAK_GBS, "unit": "GB/s",
+                     "frac": achieved / HBM_PEAK_GBS,
+                     "traffic": args.traffic_bytes,
+                     "algorithmic_bytes_per_launch": attn_bytes,
+                     "avg_launch_ms": float(attn_ms.mean())},
+    }
+    if not args.no_cpu_baseline:
+        result["cpu_baseline"] = cpu_baseline(inp)
+        log(f"cpu_baseline: {result['cpu_baseline']}")
+    print(json.dumps(result), flush=True)
+
+
+if __name__ == "__main__":
+    main()

@@ -1,0 +1,152 @@
+/*
+ * gh_tier2.h -- C ABI of the Tier-2 attention step on one MI355X (gfx950).
+ *
+ * The step is stage F2(C_k, qkv) -> C_k, x'_k of a transformer layer (paper
+ * Section 2.1): the new key/value row of each sequence is appended to that
+ * sequence's context slot, then the sequence's query heads attend over the
+ * slot (Appendix A, Table 5, rows "Q_i^T.K_i" and "A_i^T.V_i"; Section 4.3:
+ * multi-head attention with grouped-query support, FP32 arithmetic).  A
+ * sequence is addressed by a context-slot id and the position of its latest
+ * token (Section 4.1.3).  Sequences of one batch have different lengths.
+ *
+ * Conventions
+ *   - gh_problem is read on the host.  Every other pointer is a DEVICE
+ *     pointer unless stated otherwise.  The library allocates and frees
+ *     nothing: the caller owns caches, inputs, outputs, the workspace, the
+ *     index arrays and the stream.
+ *   - All calls are asynchronous on `hip_stream` (a hipStream_t, 0 = the
+ *     null stream).  append -> attention -> reduce in stream order gives
+ *     "append before attending".
+ *   - 16-bit tensors (q, k_new, v_new, caches) share one dtype (gh_dtype).
+ *     Their base addresses and all three cache strides must be multiples of
+ *     16 bytes (8 elements).
+ *   - Cache element (slot s, kv head g, row r, column j) lives at index
+ *     s*slot_stride + g*head_stride + r*row_stride + j (in elements); the
+ *     `head_dim` elements of one row are contiguous.  K and V are separate
+ *     allocations with the same geometry.
+ *   - Query head h reads kv head h / (n_q_heads / n_kv_heads).
+ *   - Host-checkable mistakes return a negative gh_status and launch
+ *     nothing.  Conditions only visible on the device (slot id or position
+ *     out of range) make the kernel skip that sequence and OR a bit into
+ *     *dev_status when that pointer is non-null.  Nothing aborts or prints.
+ *   - Caller guarantees (undefined otherwise): slot ids are unique within a
+ *     batch, buffers do not alias, ctx_len[b] <= max_ctx_len.
+ */
+#ifndef GH_TIER2_H
+#define GH_TIER2_H
+
+#include <stddef.h>
+#include <stdint.h>
+
+#ifdef __cplusplus
+extern "C" {
+#endif
+
+typedef enum {
+  GH_OK = 0,
+  GH_ERR_NULL = -1,        /* a required pointer is null                        */
+  GH_ERR_SHAPE = -2,       /* negative sizes, H % H_kv != 0, bad strides        */
+  GH_ERR_UNSUPPORTED = -3, /* head_dim != 128, unknown dtype/kernel, alignment  */
+  GH_ERR_WORKSPACE = -4,   /* workspace smaller than gh_decode_workspace_bytes  */
+  GH_ERR_CAPACITY = -5,    /* max_ctx_len > slot_capacity                       */
+  GH_ERR_HIP = -6          /* the HIP runtime refused the launch                */
+} gh_status;
+
+typedef enum { GH_F16 = 0, GH_BF16 = 1 } gh_dtype;
+
+/* Which attention kernel gh_decode_attention launches. */
+typedef enum {
+  GH_KERNEL_AUTO = 0, /* the library's measured choice for the head-group size  */
+  GH_KERNEL_VALU = 1, /* fp32 vector arithmetic, any group size                  */
+  GH_KERNEL_MFMA = 2  /* matrix-core tiles (16 heads per pass)                   */
+} gh_kernel;
+
+/* Bits OR-ed into *dev_status by gh_kv_append. */
+enum { GH_DEV_BAD_SLOT = 1, GH_DEV_BAD_POS = 2 };
+
+typedef struct {
+  int32_t batch;         /* B >= 0; 0 is a no-op returning GH_OK                 */
+  int32_t n_q_heads;     /* H                                                    */
+  int32_t n_kv_heads;    /* H_kv, divides H                                      */
+  int32_t head_dim;      /* 128 (anything else: GH_ERR_UNSUPPORTED)              */
+  int32_t dtype;         /* gh_dtype                                             */
+  int32_t n_slots;       /* slots in each cache                                  */
+  int32_t slot_capacity; /* rows per slot                                        */
+  int32_t max_ctx_len;   /* host-known upper bound of ctx_len[]; sizes the grid  */
+  int64_t slot_stride;   /* cache strides in elements, see above                 */
+  int64_t head_stride;
+  int64_t row_stride;
+  float scale;           /* softmax scaling of the scores, e.g. 1/sqrt(head_dim) */
+  int32_t chunk_rows;    /* rows per context chunk; 0 = library picks.  Must be
+                            a positive multiple of 64 otherwise.                 */
+  int32_t kernel;        /* gh_kernel                                            */
+} gh_problem;
+
+/* Static text for a status code (host pointer, never null). */
+const char* gh_status_string(int32_t status);
+
+/*
+ * Pure host functions: the split of the context into chunks (footnote of
+ * Section 2.2: attention parallelised along the sequence).
+ *   gh_decode_chunk_rows  rows per chunk actually used (p->chunk_rows, or the
+ *                         library's choice when that is 0); < 0 = gh_status.
+ *   gh_decode_num_chunks  C = ceil(max_ctx_len / chunk_rows), at least 1;
+ *                         < 0 = gh_status.
+ *   gh_decode_workspace_bytes  bytes of workspace the two decode calls need
+ *                         (0 if the problem is invalid or batch == 0).
+ *
+ * Workspace layout (fp32, base 16-byte aligned), with d = head_dim:
+ *   o[B][H][C][d]  then  m[B][H][C]  then  l[B][H][C]
+ * For chunk c of (sequence b, head h), over the rows r of that chunk and with
+ * t_r = scale * log2(e) * (q . K_r):
+ *   m = max_r t_r,  l = sum_r 2^(t_r - m),  o[:] = sum_r 2^(t_r - m) * V_r[:]
+ * A chunk with no rows has m = -inf, l = 0 and an unspecified o.
+ */
+int32_t gh_decode_chunk_rows(const gh_problem* p);
+int32_t gh_decode_num_chunks(const gh_problem* p);
+size_t gh_decode_workspace_bytes(const gh_problem* p);
+
+/*
+ * Append (the C_k update of F2).  For each sequence b and kv head g, copies
+ * the head_dim elements k_new[b][g][:] / v_new[b][g][:] ([B, H_kv, d],
+ * contiguous) to row pos[b] of slot slot_id[b] of k_cache / v_cache.  A bit
+ * copy: no arithmetic touches the data.  Only those rows are written.
+ * slot_id, pos: int32 [B].  dev_status: int32 on the device, may be null; the
+ * caller clears it.  Sequences with slot_id outside [0, n_slots) or pos
+ * outside [0, slot_capacity) are skipped and flagged there.
+ */
+int32_t gh_kv_append(const gh_problem* p, void* k_cache, void* v_cache,
+                     const void* k_new, const void* v_new,
+                     const int32_t* slot_id, const int32_t* pos,
+                     int32_t* dev_status, void* hip_stream);
+
+/*
+ * Split-context attention (Table 5's Q.K and A.V, fused, softmax kept as a
+ * running max and sum in fp32).  q: [B, H, d] contiguous.  ctx_len[b] = rows
+ * attended for sequence b (pos[b] + 1 after an append); rows at or beyond it
+ * are never read.  Writes every (m, l) of the workspace and the o of every
+ * non-empty chunk.  A sequence with ctx_len <= 0 or a slot id out of range
+ * produces only empty chunks.  ctx_len above min(max_ctx_len, slot_capacity)
+ * is clamped to it.
+ */
+int32_t gh_decode_attention(const gh_problem* p, const void* q,
+                            const void* k_cache, const void* v_cache,
+                            const int32_t* slot_id, const int32_t* ctx_len,
+                            void* workspace, size_t workspace_bytes,
+                            void* hip_stream);
+
+/*
+ * Merge of the chunk partials (same footnote).  Per (b, h), over the chunks
+ * with l > 0:  M = max_c m_c,
+ *   out[b][h][:] = sum_c 2^(m_c - M) * o_c[:] / sum_c 2^(m_c - M) * l_c
+ * and zeros when every chunk is empty.  out: fp32 [B, H, d] contiguous.
+ * Deterministic: fixed summation order, no atomics.  ctx_len may be null (it
+ * is not needed: empty chunks are recognised by l == 0).
+ */
+int32_t gh_decode_reduce(const gh_problem* p, const void* workspace,
+                         const int32_t* ctx_len, float* out, void* hip_stream);
+
+#ifdef __cplusplus
+}
+#endif
+#endif /* GH_TIER2_H */

@@ -1,0 +1,217 @@
+// Split-context decode attention on the matrix cores (v_mfma_f32_16x16x32).
+//
+// One wave owns one (sequence, kv head, head pass, chunk) and walks it in
+// tiles of 32 rows.  No LDS and no barrier: both operands are loaded from
+// global memory straight into the register layout the MFMA wants.
+//
+// Lane numbering: hn = lane % 16, c = lane / 16.
+//
+//   scores  S^T[row][head] = sum_d K[row][d] * Q[head][d]
+//     A = K tile (16 rows x 32 d), lane (hn, c) holds 8 consecutive d of row
+//         rho(T, hn) for d-chunk 4*kk + c;  B = Q^T, lane (hn, c) holds the
+//         same d-chunk of head hn.  Four kk steps cover d = 128, two sub-tiles
+//         T cover 32 rows.  The result register i of lane (hn, c) is the score
+//         of head hn against row 16T + 4i + c of the tile (rho is chosen so).
+//   output  O^T[col][head] = sum_row V[row][col] * P[head][row]
+//     B = P^T: lane (hn, c) needs, for its 8 contraction slots e = 4T + i,
+//         P[head hn][row 16T + 4i + c] -- exactly the scores it already holds.
+//     A = V^T: lane (hn, c) loads 16 bytes (columns 8hn .. 8hn+7) of those
+//         same 8 rows, so that one wave-wide load reads 4 consecutive rows
+//         (1 KiB contiguous); an in-register 8x8 transpose of 16-bit values
+//         (v_perm_b32) turns them into the operand of column tile t, which
+//         stands for columns 8*hn + t.  Result register i of lane (hn, c) in
+//         tile t is column 32c + 8i + t of head hn.
+//   So a lane's softmax state (running max m, partial sum l) and its 32 output
+//   columns all belong to one head, and rescaling needs no cross-lane traffic
+//   beyond the maximum over the four lanes of a head.
+//
+// The probabilities are split as p = hi + lo (both in the 16-bit type) and
+// multiplied in two MFMAs, so that rounding p to 8 or 11 bits of mantissa does
+// not reach the output; K.Q products are exact in fp32.
+#pragma once
+#include "gh_common.hpp"
+
+namespace gh {
+
+typedef float f32x4 __attribute__((ext_vector_type(4)));
+typedef __bf16 bf16x8 __attribute__((ext_vector_type(8)));
+typedef _Float16 f16x8 __attribute__((ext_vector_type(8)));
+typedef uint32_t u32x4 __attribute__((ext_vector_type(4)));
+
+template <bool BF16>
+__device__ __forceinline__ f32x4 mfma(const u32x4& a, const u32x4& b, const f32x4& c) {
+  if constexpr (BF16)
+    return __builtin_amdgcn_mfma_f32_16x16x32_bf16(__builtin_bit_cast(bf16x8, a),
+                                                   __builtin_bit_cast(bf16x8, b), c, 0, 0, 0);
+  else
+    return __builtin_amdgcn_mfma_f32_16x16x32_f16(__builtin_bit_cast(f16x8, a),
+                                                  __builtin_bit_cast(f16x8, b), c, 0, 0, 0);
+}
+
+// Two fp32 probabilities -> packed 16-bit pair (x low, y high), round to nearest even.
+template <bool BF16>
+__device__ __forceinline__ uint32_t pack2(float x, float y) {
+  if constexpr (BF16) {
+    typedef __bf16 b2 __attribute__((ext_vector_type(2)));
+    b2 v = {(__bf16)x, (__bf16)y};
+    return __builtin_bit_cast(uint32_t, v);
+  } else {
+    typedef _Float16 h2 __attribute__((ext_vector_type(2)));
+    h2 v = {(_Float16)x, (_Float16)y};
+    return __builtin_bit_cast(uint32_t, v);
+  }
+}
+
+// K and V registers of one 32-row tile.
+struct TileRegs {
+  u32x4 k[2][4];   // [sub-tile T][d step kk]
+  u32x4 v[8];      // [contraction slot e = 4T + i]
+};
+
+__device__ __forceinline__ void load_tile(TileRegs& t, const uint16_t* kbase, const uint16_t* vbase,
+                                          int64_t row_stride, int tile_row0, int last, int hn, int c) {
+#pragma unroll
+  for (int T = 0; T < 2; ++T) {
+    int row = tile_row0 + 16 * T + 4 * (hn & 3) + (hn >> 2);     // rho(T, hn)
+    row = row < last ? row : last;
+    const uint16_t* kp = kbase + (int64_t)row * row_stride + 8 * c;
+#pragma unroll
+    for (int kk = 0; kk < 4; ++kk)
+      t.k[T][kk] = *reinterpret_cast<const u32x4*>(kp + 32 * kk);  // d-chunk 4kk + c
+  }
+#pragma unroll
+  for (int e = 0; e < 8; ++e) {
+    int row = tile_row0 + 16 * (e >> 2) + 4 * (e & 3) + c;
+    row = row < last ? row : last;
+    t.v[e] = *reinterpret_cast<const u32x4*>(vbase + (int64_t)row * row_stride + 8 * hn);
+  }
+}
+
+template <bool BF16>
+__device__ __forceinline__ void process_tile(const TileRegs& t, const u32x4 (&qop)[4], f32x4 (&acc)[8],
+                                             float& m, float& l, float scale_log2e, int tile_row0,
+                                             int r1, int c) {
+  // scores of head hn against this lane's 8 rows
+  f32x4 s[2];
+#pragma unroll
+  for (int T = 0; T < 2; ++T) {
+    s[T] = f32x4{0.f, 0.f, 0.f, 0.f};
+#pragma unroll
+    for (int kk = 0; kk < 4; ++kk) s[T] = mfma<BF16>(t.k[T][kk], qop[kk], s[T]);
+  }
+  float tv[8];
+  float mx = kNegInf;
+#pragma unroll
+  for (int e = 0; e < 8; ++e) {
+    const int row = tile_row0 + 16 * (e >> 2) + 4 * (e & 3) + c;
+    tv[e] = row < r1 ? s[e >> 2][e & 3] * scale_log2e : kNegInf;
+    mx = fmaxf(mx, tv[e]);
+  }
+  mx = fmaxf(mx, xor16(mx));
+  mx = fmaxf(mx, xor32(mx));           // the tile has at least one row, so mx is finite
+  const float mn = fmaxf(m, mx);
+  const float alpha = fast_exp2(m - mn);
+  m = mn;
+  float sum = 0.f;
+  float lo[8];
+#pragma unroll
+  for (int e = 0; e < 8; ++e) {
+    tv[e] = fast_exp2(tv[e] - mn);
+    sum += tv[e];
+  }
+  l = fmaf(l, alpha, sum);
+  u32x4 p_hi, p_lo;
+#pragma unroll
+  for (int w = 0; w < 4; ++w) {
+    const uint32_t hi = pack2<BF16>(tv[2 * w], tv[2 * w + 1]);
+    float h0, h1;
+    unpack2<BF16>(hi, h0, h1);
+    lo[2 * w] = tv[2 * w] - h0;
+    lo[2 * w + 1] = tv[2 * w + 1] - h1;
+    p_hi[w] = hi;
+    p_lo[w] = pack2<BF16>(lo[2 * w], lo[2 * w + 1]);
+  }
+  if (__any(alpha != 1.f)) {
+#pragma unroll
+    for (int tcol = 0; tcol < 8; ++tcol) acc[tcol] *= alpha;
+  }
+  // O^T += V^T P^T, one 16-column tile at a time
+#pragma unroll
+  for (int tcol = 0; tcol < 8; ++tcol) {
+    u32x4 vt;
+#pragma unroll
+    for (int w = 0; w < 4; ++w) {
+      // 16-bit halves of two rows' registers -> (row 2w, row 2w+1) pair of column tcol
+      const uint32_t even = t.v[2 * w][tcol >> 1], odd = t.v[2 * w + 1][tcol >> 1];
+      vt[w] = (tcol & 1) ? ((even >> 16) | (odd & 0xffff0000u)) : ((even & 0xffffu) | (odd << 16));
+    }
+    acc[tcol] = mfma<BF16>(vt, p_hi, acc[tcol]);
+    acc[tcol] = mfma<BF16>(vt, p_lo, acc[tcol]);
+  }
+}
+
+template <bool BF16>
+__global__ __launch_bounds__(64) void attn_mfma_kernel(const AttnArgs a) {
+  const Item it = decode_item(a, blockIdx.x);
+  const int lane = threadIdx.x;
+  const int hn = lane & 15, c = lane >> 4;
+  if (it.r1 <= it.r0) {
+    if (lane < it.nh) {
+      const int64_t pi = partial_index(a, it, it.h0 + lane);
+      a.ws_m[pi] = kNegInf;
+      a.ws_l[pi] = 0.f;
+    }
+    return;
+  }
+
+  // Q operand: d-chunk 4kk + c of head hn (zeros for the padding heads).
+  u32x4 qop[4];
+#pragma unroll
+  for (int kk = 0; kk < 4; ++kk) {
+    qop[kk] = u32x4{0u, 0u, 0u, 0u};
+    if (hn < it.nh)
+      qop[kk] = *reinterpret_cast<const u32x4*>(
+          a.q + ((int64_t)it.b * a.n_q_heads + it.h0 + hn) * kHeadDim + 32 * kk + 8 * c);
+  }
+
+  f32x4 acc[8];
+#pragma unroll
+  for (int tcol = 0; tcol < 8; ++tcol) acc[tcol] = f32x4{0.f, 0.f, 0.f, 0.f};
+  float m = kNegInf, l = 0.f;
+
+  const uint16_t* kbase = a.k_cache + it.strip;
+  const uint16_t* vbase = a.v_cache + it.strip;
+  const int last = it.r1 - 1;
+
+  TileRegs ta, tb;
+  load_tile(ta, kbase, vbase, a.row_stride, it.r0, last, hn, c);
+  for (int row0 = it.r0; row0 < it.r1; row0 += 64) {
+    const bool has_b = row0 + 32 < it.r1;
+    if (has_b) load_tile(tb, kbase, vbase, a.row_stride, row0 + 32, last, hn, c);
+    process_tile<BF16>(ta, qop, acc, m, l, a.scale_log2e, row0, it.r1, c);
+    if (row0 + 64 < it.r1) load_tile(ta, kbase, vbase, a.row_stride, row0 + 64, last, hn, c);
+    if (has_b) process_tile<BF16>(tb, qop, acc, m, l, a.scale_log2e, row0 + 32, it.r1, c);
+  }
+
+  // The four lanes of a head share m; add up their partial sums.
+  l += xor16(l);
+  l += xor32(l);
+  if (hn < it.nh) {
+    const int64_t pi = partial_index(a, it, it.h0 + hn);
+    float* op = a.ws_o + pi * kHeadDim + 32 * c;
+#pragma unroll
+    for (int i = 0; i < 4; ++i) {
+      // register i of column tile t is column 32c + 8i + t
+      const float4 x0 = make_float4(acc[0][i], acc[1][i], acc[2][i], acc[3][i]);
+      const float4 x1 = make_float4(acc[4][i], acc[5][i], acc[6][i], acc[7][i]);
+      *reinterpret_cast<float4*>(op + 8 * i) = x0;
+      *reinterpret_cast<float4*>(op + 8 * i + 4) = x1;
+    }
+    if (c == 0) {
+      a.ws_m[pi] = m;
+      a.ws_l[pi] = l;
+    }
+  }
+}
+
+}  // namespace gh

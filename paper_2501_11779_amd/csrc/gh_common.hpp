@@ -1,0 +1,110 @@
+// Shared device-side definitions of the Tier-2 attention kernels (gfx950 only).
+#pragma once
+#include <hip/hip_runtime.h>
+#include <stdint.h>
+
+namespace gh {
+
+constexpr int kHeadDim = 128;        // columns per K/V row
+constexpr int kRowBytes = 256;       // head_dim * 2 bytes
+constexpr float kNegInf = -__builtin_huge_valf();
+
+// Arguments of both attention kernels (passed by value).
+struct AttnArgs {
+  const uint16_t* q;        // [B, H, 128]
+  const uint16_t* k_cache;
+  const uint16_t* v_cache;
+  const int32_t* slot_id;   // [B]
+  const int32_t* ctx_len;   // [B]
+  float* ws_o;              // [B, H, C, 128]
+  float* ws_m;              // [B, H, C]
+  float* ws_l;              // [B, H, C]
+  int64_t slot_stride, head_stride, row_stride;   // elements
+  int32_t n_q_heads, n_kv_heads, group;           // H, H_kv, G = H / H_kv
+  int32_t n_slots, row_limit;                     // row_limit = min(capacity, max_ctx_len)
+  int32_t chunk_rows, n_chunks;
+  int32_t heads_per_pass, n_pass;                 // head sub-groups of one kv head
+  int32_t n_items;                                // B * H_kv * n_pass * n_chunks
+  float scale_log2e;                              // scale * log2(e)
+};
+
+// One unit of work: (sequence, kv head, head pass, chunk).  The chunk index
+// varies fastest so that the chunks of one strip are in flight together.
+struct Item {
+  int b, g, pass, chunk;
+  int h0, nh;      // first query head of this pass and how many are real
+  int r0, r1;      // rows [r0, r1) of the strip; r1 <= r0 means empty
+  int64_t strip;   // element offset of row 0 of (slot, kv head)
+};
+
+__device__ __forceinline__ Item decode_item(const AttnArgs& a, int item) {
+  Item it;
+  it.chunk = item % a.n_chunks;
+  int rest = item / a.n_chunks;
+  it.pass = rest % a.n_pass;
+  rest /= a.n_pass;
+  it.g = rest % a.n_kv_heads;
+  it.b = rest / a.n_kv_heads;
+  it.h0 = it.g * a.group + it.pass * a.heads_per_pass;
+  const int left = a.group - it.pass * a.heads_per_pass;
+  it.nh = left < a.heads_per_pass ? left : a.heads_per_pass;
+  const int slot = a.slot_id[it.b];
+  int n = a.ctx_len[it.b];
+  n = n < a.row_limit ? n : a.row_limit;
+  if (slot < 0 || slot >= a.n_slots) n = 0;
+  it.r0 = it.chunk * a.chunk_rows;
+  const int end = it.r0 + a.chunk_rows;
+  it.r1 = n < end ? n : end;
+  it.strip = (int64_t)(slot < 0 || slot >= a.n_slots ? 0 : slot) * a.slot_stride +
+             (int64_t)it.g * a.head_stride;
+  return it;
+}
+
+__device__ __forceinline__ int64_t partial_index(const AttnArgs& a, const Item& it, int head) {
+  return ((int64_t)it.b * a.n_q_heads + head) * a.n_chunks + it.chunk;
+}
+
+// 2^x on the transcendental unit; 2^(-inf) = 0.
+__device__ __forceinline__ float fast_exp2(float x) { return __builtin_amdgcn_exp2f(x); }
+
+// Two packed 16-bit values -> two floats.
+template <bool BF16>
+__device__ __forceinline__ void unpack2(uint32_t w, float& lo, float& hi) {
+  if constexpr (BF16) {
+    lo = __uint_as_float(w << 16);
+    hi = __uint_as_float(w & 0xffff0000u);
+  } else {
+    typedef _Float16 h2 __attribute__((ext_vector_type(2)));
+    h2 v = __builtin_bit_cast(h2, w);
+    lo = (float)v.x;
+    hi = (float)v.y;
+  }
+}
+
+template <bool BF16>
+__device__ __forceinline__ void unpack8(const uint4& w, float (&f)[8]) {
+  unpack2<BF16>(w.x, f[0], f[1]);
+  unpack2<BF16>(w.y, f[2], f[3]);
+  unpack2<BF16>(w.z, f[4], f[5]);
+  unpack2<BF16>(w.w, f[6], f[7]);
+}
+
+// Sum over the 16 lanes of a DPP row; every lane of the row gets the total.
+__device__ __forceinline__ float row16_sum(float x) {
+  int v;
+  v = __builtin_amdgcn_update_dpp(0, __float_as_int(x), 0xB1, 0xf, 0xf, false);   // quad_perm [1,0,3,2]
+  x += __int_as_float(v);
+  v = __builtin_amdgcn_update_dpp(0, __float_as_int(x), 0x4E, 0xf, 0xf, false);   // quad_perm [2,3,0,1]
+  x += __int_as_float(v);
+  v = __builtin_amdgcn_update_dpp(0, __float_as_int(x), 0x141, 0xf, 0xf, false);  // row_half_mirror
+  x += __int_as_float(v);
+  v = __builtin_amdgcn_update_dpp(0, __float_as_int(x), 0x140, 0xf, 0xf, false);  // row_mirror
+  x += __int_as_float(v);
+  return x;
+}
+
+// Exchange with the lane 16 / 32 positions away (across the four 16-lane rows of a wave).
+__device__ __forceinline__ float xor16(float x) { return __shfl_xor(x, 16, 64); }
+__device__ __forceinline__ float xor32(float x) { return __shfl_xor(x, 32, 64); }
+
+}  // namespace gh

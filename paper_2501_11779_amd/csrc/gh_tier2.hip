@@ -1,0 +1,244 @@
+// C ABI of the Tier-2 attention step: host-side validation and kernel launches.
+// Declarations and the contract of every entry point are in include/gh_tier2.h.
+#include "gh_tier2.h"
+
+#include "gh_append.hpp"
+#include "gh_attn_mfma.hpp"
+#include "gh_attn_valu.hpp"
+#include "gh_common.hpp"
+#include "gh_reduce.hpp"
+
+namespace {
+
+constexpr int kComputeUnits = 256;          // MI355X
+constexpr int kChunkQuantum = 64;           // chunk_rows granularity
+constexpr int kMinAutoChunk = 256;
+
+int round_up(int x, int q) { return (x + q - 1) / q * q; }
+
+bool aligned16(const void* p) { return (reinterpret_cast<uintptr_t>(p) & 15u) == 0; }
+
+// Everything about gh_problem that can be judged on the host.
+int32_t check_problem(const gh_problem* p) {
+  if (!p) return GH_ERR_NULL;
+  if (p->batch < 0 || p->n_q_heads <= 0 || p->n_kv_heads <= 0 || p->n_slots <= 0 ||
+      p->slot_capacity <= 0 || p->max_ctx_len < 0)
+    return GH_ERR_SHAPE;
+  if (p->n_q_heads % p->n_kv_heads != 0) return GH_ERR_SHAPE;
+  if (p->head_dim != gh::kHeadDim) return GH_ERR_UNSUPPORTED;
+  if (p->dtype != GH_F16 && p->dtype != GH_BF16) return GH_ERR_UNSUPPORTED;
+  if (p->kernel != GH_KERNEL_AUTO && p->kernel != GH_KERNEL_VALU && p->kernel != GH_KERNEL_MFMA)
+    return GH_ERR_UNSUPPORTED;
+  if (p->row_stride < p->head_dim || p->head_stride <= 0 || p->slot_stride <= 0) return GH_ERR_SHAPE;
+  if (p->row_stride % 8 || p->head_stride % 8 || p->slot_stride % 8) return GH_ERR_UNSUPPORTED;
+  if (p->max_ctx_len > p->slot_capacity) return GH_ERR_CAPACITY;
+  if (p->chunk_rows < 0 || p->chunk_rows % kChunkQuantum != 0) return GH_ERR_SHAPE;
+  return GH_OK;
+}
+
+int resolve_kernel(const gh_problem* p) {
+  if (p->kernel != GH_KERNEL_AUTO) return p->kernel;
+  const int group = p->n_q_heads / p->n_kv_heads;
+  return group >= 2 ? GH_KERNEL_MFMA : GH_KERNEL_VALU;
+}
+
+// Heads of one kv head handled by a single work item, and how many such passes.
+void head_passes(const gh_problem* p, int kernel, int* per_pass, int* n_pass) {
+  const int group = p->n_q_heads / p->n_kv_heads;
+  int hp;
+  if (kernel == GH_KERNEL_MFMA) {
+    hp = 16;
+  } else {
+    hp = group > 4 ? 8 : group > 2 ? 4 : group;    // 1, 2, 4 or 8
+  }
+  *per_pass = hp;
+  *n_pass = (group + hp - 1) / hp;
+}
+
+// Rows per chunk: the largest multiple of the quantum that still gives the
+// chip a few work items per wave slot, but not below kMinAutoChunk rows.
+int auto_chunk_rows(const gh_problem* p) {
+  const int whole = round_up(p->max_ctx_len > 0 ? p->max_ctx_len : 1, kChunkQuantum);
+  int per_pass, n_pass;
+  head_passes(p, resolve_kernel(p), &per_pass, &n_pass);
+  const int64_t strips = (int64_t)(p->batch > 0 ? p->batch : 1) * p->n_kv_heads * n_pass;
+  const int64_t want_items = (int64_t)kComputeUnits * 32;
+  int64_t chunks = (want_items + strips - 1) / strips;       // chunks per strip wanted
+  if (chunks < 1) chunks = 1;
+  int rows = round_up((int)((whole + chunks - 1) / chunks), kChunkQuantum);
+  if (rows < kMinAutoChunk) rows = kMinAutoChunk;
+  if (rows > whole) rows = whole;
+  return rows;
+}
+
+struct Plan {
+  int kernel, chunk_rows, n_chunks, per_pass, n_pass;
+};
+
+Plan make_plan(const gh_problem* p) {
+  Plan pl;
+  pl.kernel = resolve_kernel(p);
+  pl.chunk_rows = p->chunk_rows > 0 ? p->chunk_rows : auto_chunk_rows(p);
+  pl.n_chunks = p->max_ctx_len > 0 ? (p->max_ctx_len + pl.chunk_rows - 1) / pl.chunk_rows : 1;
+  head_passes(p, pl.kernel, &pl.per_pass, &pl.n_pass);
+  return pl;
+}
+
+size_t workspace_floats(const gh_problem* p, const Plan& pl) {
+  return (size_t)p->batch * p->n_q_heads * pl.n_chunks * (gh::kHeadDim + 2);
+}
+
+template <bool BF16>
+void launch_valu(const gh::AttnArgs& a, int per_pass, hipStream_t s) {
+  const dim3 grid(a.n_items), block(256);
+  switch (per_pass) {
+    case 1: hipLaunchKernelGGL((gh::attn_valu_kernel<1, BF16>), grid, block, 0, s, a); break;
+    case 2: hipLaunchKernelGGL((gh::attn_valu_kernel<2, BF16>), grid, block, 0, s, a); break;
+    case 4: hipLaunchKernelGGL((gh::attn_valu_kernel<4, BF16>), grid, block, 0, s, a); break;
+    default: hipLaunchKernelGGL((gh::attn_valu_kernel<8, BF16>), grid, block, 0, s, a); break;
+  }
+}
+
+}  // namespace
+
+extern "C" {
+
+const char* gh_status_string(int32_t status) {
+  switch (status) {
+    case GH_OK: return "ok";
+    case GH_ERR_NULL: return "a required pointer is null";
+    case GH_ERR_SHAPE: return "inconsistent sizes, head counts, strides or chunk_rows";
+    case GH_ERR_UNSUPPORTED: return "unsupported head_dim, dtype, kernel or alignment";
+    case GH_ERR_WORKSPACE: return "workspace too small";
+    case GH_ERR_CAPACITY: return "max_ctx_len exceeds slot_capacity";
+    case GH_ERR_HIP: return "HIP launch failed";
+    default: return "unknown status";
+  }
+}
+
+int32_t gh_decode_chunk_rows(const gh_problem* p) {
+  const int32_t st = check_problem(p);
+  if (st != GH_OK) return st;
+  return make_plan(p).chunk_rows;
+}
+
+int32_t gh_decode_num_chunks(const gh_problem* p) {
+  const int32_t st = check_problem(p);
+  if (st != GH_OK) return st;
+  return make_plan(p).n_chunks;
+}
+
+size_t gh_decode_workspace_bytes(const gh_problem* p) {
+  if (check_problem(p) != GH_OK) return 0;
+  return workspace_floats(p, make_plan(p)) * sizeof(float);
+}
+
+int32_t gh_kv_append(const gh_problem* p, void* k_cache, void* v_cache, const void* k_new,
+                     const void* v_new, const int32_t* slot_id, const int32_t* pos,
+                     int32_t* dev_status, void* hip_stream) {
+  const int32_t st = check_problem(p);
+  if (st != GH_OK) return st;
+  if (p->batch == 0) return GH_OK;
+  if (!k_cache || !v_cache || !k_new || !v_new || !slot_id || !pos) return GH_ERR_NULL;
+  if (!aligned16(k_cache) || !aligned16(v_cache) || !aligned16(k_new) || !aligned16(v_new))
+    return GH_ERR_UNSUPPORTED;
+  gh::AppendArgs a;
+  a.k_cache = static_cast<uint16_t*>(k_cache);
+  a.v_cache = static_cast<uint16_t*>(v_cache);
+  a.k_new = static_cast<const uint16_t*>(k_new);
+  a.v_new = static_cast<const uint16_t*>(v_new);
+  a.slot_id = slot_id;
+  a.pos = pos;
+  a.dev_status = dev_status;
+  a.slot_stride = p->slot_stride;
+  a.head_stride = p->head_stride;
+  a.row_stride = p->row_stride;
+  a.batch = p->batch;
+  a.n_kv_heads = p->n_kv_heads;
+  a.n_slots = p->n_slots;
+  a.capacity = p->slot_capacity;
+  const int64_t threads = (int64_t)p->batch * p->n_kv_heads * 32;
+  const dim3 grid((unsigned)((threads + 255) / 256)), block(256);
+  hipLaunchKernelGGL(gh::kv_append_kernel, grid, block, 0, static_cast<hipStream_t>(hip_stream), a);
+  return hipGetLastError() == hipSuccess ? GH_OK : GH_ERR_HIP;
+}
+
+int32_t gh_decode_attention(const gh_problem* p, const void* q, const void* k_cache,
+                            const void* v_cache, const int32_t* slot_id, const int32_t* ctx_len,
+                            void* workspace, size_t workspace_bytes, void* hip_stream) {
+  const int32_t st = check_problem(p);
+  if (st != GH_OK) return st;
+  if (p->batch == 0) return GH_OK;
+  if (!q || !k_cache || !v_cache || !slot_id || !ctx_len || !workspace) return GH_ERR_NULL;
+  if (!aligned16(q) || !aligned16(k_cache) || !aligned16(v_cache) || !aligned16(workspace))
+    return GH_ERR_UNSUPPORTED;
+  const Plan pl = make_plan(p);
+  const size_t nrec = (size_t)p->batch * p->n_q_heads * pl.n_chunks;
+  if (workspace_bytes < workspace_floats(p, pl) * sizeof(float)) return GH_ERR_WORKSPACE;
+  const int64_t items = (int64_t)p->batch * p->n_kv_heads * pl.n_pass * pl.n_chunks;
+  if (items > 0x7fffffff) return GH_ERR_SHAPE;
+
+  gh::AttnArgs a;
+  a.q = static_cast<const uint16_t*>(q);
+  a.k_cache = static_cast<const uint16_t*>(k_cache);
+  a.v_cache = static_cast<const uint16_t*>(v_cache);
+  a.slot_id = slot_id;
+  a.ctx_len = ctx_len;
+  a.ws_o = static_cast<float*>(workspace);
+  a.ws_m = a.ws_o + nrec * gh::kHeadDim;
+  a.ws_l = a.ws_m + nrec;
+  a.slot_stride = p->slot_stride;
+  a.head_stride = p->head_stride;
+  a.row_stride = p->row_stride;
+  a.n_q_heads = p->n_q_heads;
+  a.n_kv_heads = p->n_kv_heads;
+  a.group = p->n_q_heads / p->n_kv_heads;
+  a.n_slots = p->n_slots;
+  a.row_limit = p->max_ctx_len < p->slot_capacity ? p->max_ctx_len : p->slot_capacity;
+  a.chunk_rows = pl.chunk_rows;
+  a.n_chunks = pl.n_chunks;
+  a.heads_per_pass = pl.per_pass;
+  a.n_pass = pl.n_pass;
+  a.n_items = (int32_t)items;
+  a.scale_log2e = p->scale * 1.44269504088896340736f;
+
+  hipStream_t s = static_cast<hipStream_t>(hip_stream);
+  const bool bf16 = p->dtype == GH_BF16;
+  if (pl.kernel == GH_KERNEL_MFMA) {
+    const dim3 grid(a.n_items), block(64);
+    if (bf16)
+      hipLaunchKernelGGL(gh::attn_mfma_kernel<true>, grid, block, 0, s, a);
+    else
+      hipLaunchKernelGGL(gh::attn_mfma_kernel<false>, grid, block, 0, s, a);
+  } else {
+    if (bf16)
+      launch_valu<true>(a, pl.per_pass, s);
+    else
+      launch_valu<false>(a, pl.per_pass, s);
+  }
+  return hipGetLastError() == hipSuccess ? GH_OK : GH_ERR_HIP;
+}
+
+int32_t gh_decode_reduce(const gh_problem* p, const void* workspace, const int32_t* ctx_len,
+                         float* out, void* hip_stream) {
+  (void)ctx_len;
+  const int32_t st = check_problem(p);
+  if (st != GH_OK) return st;
+  if (p->batch == 0) return GH_OK;
+  if (!workspace || !out) return GH_ERR_NULL;
+  if (!aligned16(workspace) || !aligned16(out)) return GH_ERR_UNSUPPORTED;
+  const Plan pl = make_plan(p);
+  const size_t nrec = (size_t)p->batch * p->n_q_heads * pl.n_chunks;
+  gh::ReduceArgs a;
+  a.ws_o = static_cast<const float*>(workspace);
+  a.ws_m = a.ws_o + nrec * gh::kHeadDim;
+  a.ws_l = a.ws_m + nrec;
+  a.out = out;
+  a.n_rows = (int64_t)p->batch * p->n_q_heads;
+  a.n_chunks = pl.n_chunks;
+  const dim3 grid((unsigned)((a.n_rows + 3) / 4)), block(256);
+  hipLaunchKernelGGL(gh::decode_reduce_kernel, grid, block, 0, static_cast<hipStream_t>(hip_stream), a);
+  return hipGetLastError() == hipSuccess ? GH_OK : GH_ERR_HIP;
+}
+
+}  // extern "C"

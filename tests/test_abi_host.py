@@ -1,0 +1,126 @@
+"""Host-side checks of the C ABI that need no GPU: exports, validation, chunk planning."""
+import ctypes as C
+import os
+import re
+
+import pytest
+
+from paper_2501_11779_amd import binding as G
+
+ROOT = os.path.dirname(os.path.dirname(os.path.abspath(__file__)))
+
+
+def _declared_functions():
+    text = open(os.path.join(ROOT, "include", "gh_tier2.h")).read()
+    text = re.sub(r"/\*.*?\*/", "", text, flags=re.S)
+    return sorted(set(re.findall(r"\b(gh_[a-z_0-9]+)\s*\(", text)))
+
+
+def good(**kw):
+    base = dict(batch=4, n_q_heads=32, n_kv_heads=8, head_dim=128, dtype=G.GH_BF16, n_slots=4,
+                slot_capacity=4097, max_ctx_len=4097, strides=(8 * 4097 * 128, 4097 * 128, 128),
+                scale=128 ** -0.5, chunk_rows=0, kernel=G.GH_KERNEL_AUTO)
+    base.update(kw)
+    return G.make_problem(**base)
+
+
+def test_library_loads_and_exports_every_declared_symbol():
+    names = _declared_functions()
+    assert set(names) == set(G.EXPORTS)
+    L = G.lib()
+    for n in names:
+        assert getattr(L, n) is not None
+
+
+def test_status_strings():
+    for st in range(0, -7, -1):
+        assert G.gh_status_string(st) not in ("", "unknown status")
+    assert G.gh_status_string(-99) == "unknown status"
+
+
+@pytest.mark.parametrize("kw,status", [
+    (dict(n_kv_heads=5), G.GH_ERR_SHAPE),
+    (dict(batch=-1), G.GH_ERR_SHAPE),
+    (dict(n_slots=0), G.GH_ERR_SHAPE),
+    (dict(head_dim=64), G.GH_ERR_UNSUPPORTED),
+    (dict(dtype=7), G.GH_ERR_UNSUPPORTED),
+    (dict(kernel=9), G.GH_ERR_UNSUPPORTED),
+    (dict(strides=(8 * 4097 * 128, 4097 * 128, 64)), G.GH_ERR_SHAPE),
+    (dict(strides=(8 * 4097 * 128 + 4, 4097 * 128, 128)), G.GH_ERR_UNSUPPORTED),
+    (dict(max_ctx_len=5000), G.GH_ERR_CAPACITY),
+    (dict(chunk_rows=100), G.GH_ERR_SHAPE),
+    (dict(chunk_rows=-64), G.GH_ERR_SHAPE),
+])
+def test_invalid_problems_are_refused_by_every_entry_point(kw, status):
+    p = good(**kw)
+    assert G.gh_decode_chunk_rows(p) == status
+    assert G.gh_decode_num_chunks(p) == status
+    assert G.gh_decode_workspace_bytes(p) == 0
+    fake = 4096  # never dereferenced: validation fails first
+    assert G.gh_kv_append(p, fake, fake, fake, fake, fake, fake, None, 0) == status
+    assert G.gh_decode_attention(p, fake, fake, fake, fake, fake, fake, 1 << 40, 0) == status
+    assert G.gh_decode_reduce(p, fake, None, fake, 0) == status
+
+
+def test_null_problem_and_null_pointers():
+    L = G.lib()
+    assert L.gh_decode_chunk_rows(None) == G.GH_ERR_NULL
+    assert L.gh_kv_append(None, 1, 1, 1, 1, 1, 1, None, None) == G.GH_ERR_NULL
+    p = good()
+    a = 4096
+    assert G.gh_kv_append(p, None, a, a, a, a, a, None, 0) == G.GH_ERR_NULL
+    assert G.gh_kv_append(p, a, a, a, a, None, a, None, 0) == G.GH_ERR_NULL
+    assert G.gh_decode_attention(p, a, a, a, a, None, a, 1 << 40, 0) == G.GH_ERR_NULL
+    assert G.gh_decode_attention(p, a, a, a, a, a, None, 1 << 40, 0) == G.GH_ERR_NULL
+    assert G.gh_decode_reduce(p, None, None, a, 0) == G.GH_ERR_NULL
+    assert G.gh_decode_reduce(p, a, None, None, 0) == G.GH_ERR_NULL
+
+
+def test_misaligned_pointers_and_small_workspace():
+    p = good()
+    a = 4096
+    assert G.gh_kv_append(p, a + 2, a, a, a, a, a, None, 0) == G.GH_ERR_UNSUPPORTED
+    assert G.gh_decode_attention(p, a + 8, a, a, a, a, a, 1 << 40, 0) == G.GH_ERR_UNSUPPORTED
+    need = G.gh_decode_workspace_bytes(p)
+    assert need > 0
+    assert G.gh_decode_attention(p, a, a, a, a, a, a, need - 1, 0) == G.GH_ERR_WORKSPACE
+
+
+def test_empty_batch_is_a_no_op():
+    p = good(batch=0)
+    assert G.gh_kv_append(p, None, None, None, None, None, None, None, 0) == G.GH_OK
+    assert G.gh_decode_attention(p, None, None, None, None, None, None, 0, 0) == G.GH_OK
+    assert G.gh_decode_reduce(p, None, None, None, 0) == G.GH_OK
+    assert G.gh_decode_workspace_bytes(p) == 0
+
+
+@pytest.mark.parametrize("kernel", [G.GH_KERNEL_AUTO, G.GH_KERNEL_VALU, G.GH_KERNEL_MFMA])
+@pytest.mark.parametrize("B,H,Hkv,maxlen", [(4, 8, 8, 513), (64, 32, 32, 2049), (256, 32, 8, 4097),
+                                           (1024, 64, 8, 4097), (32, 64, 8, 32769), (1, 1, 1, 1)])
+def test_chunk_plan_is_consistent(kernel, B, H, Hkv, maxlen):
+    p = good(batch=B, n_q_heads=H, n_kv_heads=Hkv, n_slots=B, slot_capacity=maxlen,
+             max_ctx_len=maxlen, strides=(Hkv * maxlen * 128, maxlen * 128, 128), kernel=kernel)
+    rows = G.gh_decode_chunk_rows(p)
+    n = G.gh_decode_num_chunks(p)
+    assert rows > 0 and rows % 64 == 0
+    assert n == -(-maxlen // rows) and n >= 1
+    assert G.gh_decode_workspace_bytes(p) == B * H * n * (128 + 2) * 4
+    # a forced chunk size is taken as given
+    p.chunk_rows = 128
+    assert G.gh_decode_chunk_rows(p) == 128
+    assert G.gh_decode_num_chunks(p) == -(-maxlen // 128)
+
+
+def test_problem_struct_matches_header_field_order():
+    text = open(os.path.join(ROOT, "include", "gh_tier2.h")).read()
+    body = re.search(r"typedef struct \{(.*?)\} gh_problem;", text, flags=re.S).group(1)
+    body = re.sub(r"/\*.*?\*/", "", body, flags=re.S)
+    fields = []
+    for decl in body.split(";"):
+        decl = decl.strip()
+        if not decl:
+            continue
+        ctype, names = decl.split(None, 1)
+        fields += [(n.strip(), ctype) for n in names.split(",")]
+    want = {"int32_t": C.c_int32, "int64_t": C.c_int64, "float": C.c_float}
+    assert [(n, want[t]) for n, t in fields] == list(G.gh_problem._fields_)

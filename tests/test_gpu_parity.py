@@ -1,0 +1,293 @@
+"""GPU parity: every entry point of the C ABI against the CPU oracle on seeded inputs.
+
+Small cases compare the whole output element by element; the full-size workloads compare
+sampled sequences (the oracle recomputes each sampled sequence on its own) in the launch
+configuration the benchmark times.  Tolerance for attention: max-abs 2e-3 and relative L2 1e-3
+(16-bit K/V, fp32 accumulation); the append is compared bit for bit.
+"""
+import math
+
+import numpy as np
+import pytest
+import torch
+
+from oracle import gh_oracle as O
+from paper_2501_11779_amd import binding as G
+from paper_2501_11779_amd import workloads as W
+from tests import helpers as Hh
+
+pytestmark = pytest.mark.gpu
+
+DEV = "cuda"
+KERNELS = {"valu": G.GH_KERNEL_VALU, "mfma": G.GH_KERNEL_MFMA}
+
+
+def small(name, B, H, Hkv, dtype, seed):
+    return W.Workload(name, B, H, Hkv, 128, dtype, ("const", 0), seed)
+
+
+def run_gpu(inp, chunk_rows=0, kernel=G.GH_KERNEL_AUTO, append=True, status=None):
+    p = G.problem_from_inputs(inp, chunk_rows=chunk_rows, kernel=kernel)
+    w = inp["workload"]
+    ws = G.alloc_workspace(p, DEV)
+    out = torch.full((w.batch, w.n_q_heads, w.head_dim), float("nan"), dtype=torch.float32,
+                     device=DEV)
+    G.decode_step(p, inp, ws, out, dev_status=status, append=append)
+    torch.cuda.synchronize()
+    return out.cpu().numpy(), p, ws
+
+
+# ------------------------------------------------------------------ append
+@pytest.mark.parametrize("layout", ["head_major", "token_major"])
+@pytest.mark.parametrize("dtype", ["f16", "bf16"])
+def test_append_bit_exact_whole_cache(layout, dtype):
+    w = small("app", 5, 8, 4, dtype, 31)
+    L = np.array([0, 7, 63, 64, 129], dtype=np.int32)
+    inp = W.make_inputs(w, DEV, lengths=L, n_slots=7, capacity=131, layout=layout)
+    host = Hh.host_copy(inp)
+    p = G.problem_from_inputs(inp)
+    status = torch.zeros(1, dtype=torch.int32, device=DEV)
+    G.check(G.gh_kv_append(p, inp["k_cache"], inp["v_cache"], inp["k_new"], inp["v_new"],
+                           inp["slot_id"], inp["pos"], status))
+    torch.cuda.synchronize()
+    po = Hh.oracle_problem(inp)
+    assert O.kv_append(po, host["k_cache"], host["v_cache"], host["k_new"], host["v_new"],
+                       host["slot_id"], host["pos"]) == 0
+    assert np.array_equal(W.bits(inp["k_cache"]), host["k_cache"])
+    assert np.array_equal(W.bits(inp["v_cache"]), host["v_cache"])
+    assert status.item() == 0
+
+
+def test_append_flags_and_skips_bad_slot_or_position():
+    w = small("bad", 4, 4, 2, "bf16", 32)
+    inp = W.make_inputs(w, DEV, lengths=np.array([3, 4, 5, 6], dtype=np.int32), n_slots=4,
+                        capacity=8)
+    inp["slot_id"][1] = 9           # no such slot
+    inp["pos"][2] = 8               # one past the capacity
+    host = Hh.host_copy(inp)
+    p = G.problem_from_inputs(inp)
+    status = torch.zeros(1, dtype=torch.int32, device=DEV)
+    G.check(G.gh_kv_append(p, inp["k_cache"], inp["v_cache"], inp["k_new"], inp["v_new"],
+                           inp["slot_id"], inp["pos"], status))
+    torch.cuda.synchronize()
+    assert status.item() == (G.GH_DEV_BAD_SLOT | G.GH_DEV_BAD_POS)
+    po = Hh.oracle_problem(inp)
+    assert O.kv_append(po, host["k_cache"], host["v_cache"], host["k_new"], host["v_new"],
+                       host["slot_id"], host["pos"]) == 2
+    assert np.array_equal(W.bits(inp["k_cache"]), host["k_cache"])
+    assert np.array_equal(W.bits(inp["v_cache"]), host["v_cache"])
+
+
+# ------------------------------------------------------------------ attention, small, whole output
+RAGGED = np.array([0, 1, 30, 31, 32, 62, 63, 64, 65, 127, 128, 191, 299, 512, 700], dtype=np.int32)
+
+
+@pytest.mark.parametrize("kernel", ["valu", "mfma"])
+@pytest.mark.parametrize("dtype", ["f16", "bf16"])
+@pytest.mark.parametrize("H,Hkv", [(4, 4), (4, 2), (8, 2), (8, 1), (6, 2), (32, 2), (40, 2)])
+@pytest.mark.parametrize("chunk_rows", [64, 192, 0])
+def test_attention_matches_oracle_on_ragged_batch(kernel, dtype, H, Hkv, chunk_rows):
+    w = small("rag", len(RAGGED), H, Hkv, dtype, 40 + H + Hkv)
+    inp = W.make_inputs(w, DEV, lengths=RAGGED, n_slots=len(RAGGED) + 3)
+    host = Hh.host_copy(inp)
+    got, p, _ = run_gpu(inp, chunk_rows, KERNELS[kernel])
+    want = Hh.oracle_step(inp, host)
+    Hh.assert_parity(got, want, f"{kernel} {dtype} H={H}/{Hkv} chunk={chunk_rows}")
+    # and the cache after the step is the oracle's mirror, bit for bit
+    assert np.array_equal(W.bits(inp["k_cache"]), host["k_cache"])
+    assert np.array_equal(W.bits(inp["v_cache"]), host["v_cache"])
+
+
+@pytest.mark.parametrize("kernel", ["valu", "mfma"])
+def test_token_major_layout(kernel):
+    w = small("tok", 6, 8, 2, "bf16", 50)
+    L = np.array([5, 64, 100, 257, 31, 400], dtype=np.int32)
+    inp = W.make_inputs(w, DEV, lengths=L, layout="token_major")
+    host = Hh.host_copy(inp)
+    got, _, _ = run_gpu(inp, 128, KERNELS[kernel])
+    Hh.assert_parity(got, Hh.oracle_step(inp, host), "token-major")
+
+
+@pytest.mark.parametrize("kernel", ["valu", "mfma"])
+def test_config1_whole_output(kernel):
+    inp = W.make_inputs(W.WORKLOADS["c1"], DEV)
+    host = Hh.host_copy(inp)
+    got, _, _ = run_gpu(inp, 0, KERNELS[kernel])
+    want = Hh.oracle_step(inp, host)
+    Hh.assert_parity(got, want, "c1")
+    assert np.array_equal(W.bits(inp["k_cache"]), host["k_cache"])
+    assert np.array_equal(W.bits(inp["v_cache"]), host["v_cache"])
+
+
+# ------------------------------------------------------------------ closed forms on the GPU
+@pytest.mark.parametrize("kernel", ["valu", "mfma"])
+@pytest.mark.parametrize("dtype", ["f16", "bf16"])
+def test_length_one_returns_the_value_row_exactly(kernel, dtype):
+    w = small("one", 3, 8, 2, dtype, 60)
+    inp = W.make_inputs(w, DEV, lengths=np.zeros(3, dtype=np.int32), capacity=4)
+    got, _, _ = run_gpu(inp, 0, KERNELS[kernel])
+    v_new = inp["v_new"].float().cpu().numpy()            # exact widening of the appended row
+    for h in range(8):
+        assert np.array_equal(got[:, h], v_new[:, h // 4])
+
+
+@pytest.mark.parametrize("kernel", ["valu", "mfma"])
+def test_identical_keys_give_mean_of_values(kernel):
+    w = small("mean", 2, 8, 2, "bf16", 61)
+    L = np.array([200, 77], dtype=np.int32)
+    inp = W.make_inputs(w, DEV, lengths=L, poison=False)
+    inp["k_cache"][:] = inp["k_cache"][:, :, :1, :]
+    inp["k_new"][:] = inp["k_cache"][inp["slot_id"].long(), :, 0, :]
+    got, _, _ = run_gpu(inp, 64, KERNELS[kernel])
+    v = inp["v_cache"].double().cpu().numpy()
+    for b in range(2):
+        n = L[b] + 1
+        for h in range(8):
+            want = v[inp["slots"][b], h // 4, :n].mean(axis=0)
+            assert np.abs(got[b, h] - want).max() < 5e-6
+
+
+@pytest.mark.parametrize("kernel", ["valu", "mfma"])
+def test_one_hot_row_with_huge_score_is_finite_and_selected(kernel):
+    w = small("hot", 1, 8, 1, "bf16", 62)
+    inp = W.make_inputs(w, DEV, lengths=np.array([300], dtype=np.int32))
+    # key row 123 = 4*q of head 0 would give a score of ~4*128/sqrt(128)=45 for that head
+    inp["k_cache"][inp["slots"][0], 0, 123] = inp["q"][0, 0] * 4
+    host = Hh.host_copy(inp)
+    got, _, _ = run_gpu(inp, 64, KERNELS[kernel])
+    want = Hh.oracle_step(inp, host)
+    Hh.assert_parity(got, want, "one-hot")
+    v123 = inp["v_cache"][inp["slots"][0], 0, 123].float().cpu().numpy()
+    assert np.abs(got[0, 0] - v123).max() < 1e-3
+
+
+# ------------------------------------------------------------------ robustness
+@pytest.mark.parametrize("kernel", ["valu", "mfma"])
+def test_zero_length_and_bad_slot_give_zeros_and_do_not_disturb_others(kernel):
+    w = small("zero", 4, 8, 2, "bf16", 63)
+    L = np.array([100, 50, 70, 20], dtype=np.int32)
+    inp = W.make_inputs(w, DEV, lengths=L, n_slots=6)
+    host = Hh.host_copy(inp)
+    ref, _, _ = run_gpu(inp, 64, KERNELS[kernel])
+    want = Hh.oracle_step(inp, host)
+    Hh.assert_parity(ref, want, "baseline")
+    inp["ctx_len"][1] = 0
+    inp["slot_id"][2] = 77
+    got, _, _ = run_gpu(inp, 64, KERNELS[kernel], append=False)
+    assert not got[1].any() and not got[2].any()
+    assert np.array_equal(got[0], ref[0]) and np.array_equal(got[3], ref[3])
+
+
+@pytest.mark.parametrize("kernel", ["valu", "mfma"])
+def test_bit_reproducible_and_batch_independent(kernel):
+    w = small("rep", 8, 16, 4, "f16", 64)
+    L = np.array([10, 900, 33, 257, 64, 511, 128, 700], dtype=np.int32)
+    inp = W.make_inputs(w, DEV, lengths=L)
+    a, _, _ = run_gpu(inp, 128, KERNELS[kernel])
+    b, _, _ = run_gpu(inp, 128, KERNELS[kernel], append=False)
+    assert np.array_equal(a, b)
+    # the same sequence alone in a batch of one gives the same bits
+    p1 = G.make_problem(1, 16, 4, 128, G.GH_F16, inp["n_slots"], inp["capacity"],
+                        int(L.max()) + 1, inp["strides"], inp["scale"], 128, KERNELS[kernel])
+    ws = G.alloc_workspace(p1, DEV)
+    out = torch.empty((1, 16, 128), dtype=torch.float32, device=DEV)
+    G.check(G.gh_decode_attention(p1, inp["q"][3:4].contiguous(), inp["k_cache"], inp["v_cache"],
+                                  inp["slot_id"][3:4].contiguous(),
+                                  inp["ctx_len"][3:4].contiguous(), ws))
+    G.check(G.gh_decode_reduce(p1, ws, None, out))
+    torch.cuda.synchronize()
+    assert np.array_equal(out.cpu().numpy()[0], a[3])
+
+
+# ------------------------------------------------------------------ the merge on its own
+def test_reduce_matches_oracle_merge_of_oracle_partials():
+    w = small("red", 3, 4, 2, "bf16", 65)
+    L = np.array([300, 64, 5], dtype=np.int32)
+    inp = W.make_inputs(w, "cpu", lengths=L)
+    host = Hh.host_copy(inp)
+    po = Hh.oracle_problem(inp)
+    want = Hh.oracle_step(inp, host)
+    chunk = 64
+    p = G.problem_from_inputs(inp, chunk_rows=chunk)
+    C_ = G.gh_decode_num_chunks(p)
+    B, H, d = 3, 4, 128
+    o = np.full((B, H, C_, d), np.nan, dtype=np.float32)
+    m = np.full((B, H, C_), -np.inf, dtype=np.float32)
+    l = np.zeros((B, H, C_), dtype=np.float32)
+    for b in range(B):
+        n = L[b] + 1
+        for h in range(H):
+            for c in range(C_):
+                r0, r1 = c * chunk, min(n, (c + 1) * chunk)
+                if r1 <= r0:
+                    continue
+                mm, ll, oo = O.partial(po, host["q"], host["k_cache"], host["v_cache"],
+                                       host["slot_id"], b, h, r0, r1)
+                m[b, h, c], l[b, h, c], o[b, h, c] = mm, ll, oo
+    ws = torch.from_numpy(np.concatenate([o.ravel(), m.ravel(), l.ravel()])).to(DEV)
+    out = torch.empty((B, H, d), dtype=torch.float32, device=DEV)
+    G.check(G.gh_decode_reduce(p, ws, None, out))
+    torch.cuda.synchronize()
+    assert np.abs(out.cpu().numpy() - want).max() < 2e-6
+
+
+@pytest.mark.parametrize("kernel", ["valu", "mfma"])
+def test_attention_partials_match_oracle_partials(kernel):
+    w = small("par", 2, 8, 2, "bf16", 66)
+    L = np.array([200, 70], dtype=np.int32)
+    inp = W.make_inputs(w, DEV, lengths=L)
+    host = Hh.host_copy(inp)
+    chunk = 64
+    _, p, ws = run_gpu(inp, chunk, KERNELS[kernel])
+    po = Hh.oracle_problem(inp)
+    O.kv_append(po, host["k_cache"], host["v_cache"], host["k_new"], host["v_new"],
+                host["slot_id"], host["pos"])
+    C_ = G.gh_decode_num_chunks(p)
+    B, H, d = 2, 8, 128
+    wsn = ws.cpu().numpy()
+    o = wsn[:B * H * C_ * d].reshape(B, H, C_, d)
+    m = wsn[B * H * C_ * d:B * H * C_ * (d + 1)].reshape(B, H, C_)
+    l = wsn[B * H * C_ * (d + 1):B * H * C_ * (d + 2)].reshape(B, H, C_)
+    for b in range(B):
+        n = L[b] + 1
+        for h in range(H):
+            for c in range(C_):
+                r0, r1 = c * chunk, min(n, (c + 1) * chunk)
+                if r1 <= r0:
+                    assert m[b, h, c] == -np.inf and l[b, h, c] == 0.0
+                    continue
+                mm, ll, oo = O.partial(po, host["q"], host["k_cache"], host["v_cache"],
+                                       host["slot_id"], b, h, r0, r1)
+                # (m, l, o) is defined up to the common factor 2^m: compare what is unique
+                assert abs((m[b, h, c] + math.log2(l[b, h, c])) - (mm + math.log2(ll))) < 1e-4
+                assert np.abs(o[b, h, c] / l[b, h, c] - oo / ll).max() < Hh.MAX_ABS_TOL
+
+
+# ------------------------------------------------------------------ full-size workloads, sampled
+def _sample_sequences(L, k, seed):
+    rng = np.random.default_rng(seed)
+    pick = {int(np.argmin(L)), int(np.argmax(L))}
+    pick.update(rng.choice(len(L), size=min(k, len(L)), replace=False).tolist())
+    return sorted(pick)
+
+
+@pytest.mark.parametrize("name,n_samples", [("c2", 12), ("c3", 12), ("c4", 12), ("c5", 6)])
+def test_full_size_workload_sampled_sequences(name, n_samples):
+    w = W.WORKLOADS[name]
+    inp = W.make_inputs(w, DEV)
+    picks = _sample_sequences(inp["lengths"], n_samples, w.seed)
+    slices = {b: Hh.sequence_slice(inp, b) for b in picks}        # bits before the step
+    got, p, _ = run_gpu(inp)                                       # the benchmark's launch config
+    assert np.all(np.isfinite(got))
+    worst = (0.0, 0.0)
+    for b in picks:
+        want, k_m, v_m = Hh.oracle_sequence(inp, slices[b])
+        e = Hh.assert_parity(got[b], want, f"{name} seq {b} len {inp['lengths'][b]}")
+        worst = (max(worst[0], e[0]), max(worst[1], e[1]))
+        slot = int(inp["slots"][b])
+        assert np.array_equal(W.bits(inp["k_cache"][slot:slot + 1]), k_m)
+        assert np.array_equal(W.bits(inp["v_cache"][slot:slot + 1]), v_m)
+    print(f"{name}: {len(picks)} sequences, worst max_abs={worst[0]:.2e} rel_l2={worst[1]:.2e}, "
+          f"chunk_rows={G.gh_decode_chunk_rows(p)}")
+    # properties that hold at any size: every output is a convex combination of value rows
+    assert np.abs(got).max() < 8.0
