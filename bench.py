@@ -76,6 +76,9 @@ def main():
     ap.add_argument("--kernel", default="auto", choices=["auto", "valu", "mfma"])
     ap.add_argument("--chunk-rows", type=int, default=0)
     ap.add_argument("--no-cpu-baseline", action="store_true")
+    ap.add_argument("--batch", type=int, default=0, help="experiment: override the batch size")
+    ap.add_argument("--const-len", type=int, default=0,
+                    help="experiment: every sequence has this many cached rows")
     ap.add_argument("--traffic-bytes", type=float, default=None,
                     help="HBM bytes per attention launch from rocprofv3 counters, if measured")
     args = ap.parse_args()
@@ -96,6 +99,12 @@ def main():
         f"mem={props.total_memory / 2**30:.0f} GiB host_cpus={os.cpu_count()}")
 
     w = W.WORKLOADS[args.workload]
+    if args.batch or args.const_len:
+        import dataclasses
+        w = dataclasses.replace(
+            w, batch=args.batch or w.batch,
+            lengths=("const", args.const_len) if args.const_len else w.lengths,
+            note=w.note + " [EXPERIMENT: overridden batch/lengths]")
     t0 = time.perf_counter()
     inp = W.make_inputs(w, "cuda")
     torch.cuda.synchronize()

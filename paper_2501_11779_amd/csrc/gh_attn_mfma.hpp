@@ -150,28 +150,21 @@ __device__ __forceinline__ void process_tile(const TileRegs& t, const u32x4 (&qo
   }
 }
 
+// Rows [r0, r1) (r0 < r1) of one strip for the heads h0 .. h0+nh-1 of sequence b, written as
+// partial record `slot` of those heads.
 template <bool BF16>
-__global__ __launch_bounds__(64) void attn_mfma_kernel(const AttnArgs a) {
-  const Item it = decode_item(a, blockIdx.x);
-  const int lane = threadIdx.x;
+__device__ __forceinline__ void run_strip(const AttnArgs& a, int b, int h0, int nh, int64_t strip,
+                                          int r0, int r1, int slot, int lane) {
   const int hn = lane & 15, c = lane >> 4;
-  if (it.r1 <= it.r0) {
-    if (lane < it.nh) {
-      const int64_t pi = partial_index(a, it, it.h0 + lane);
-      a.ws_m[pi] = kNegInf;
-      a.ws_l[pi] = 0.f;
-    }
-    return;
-  }
 
   // Q operand: d-chunk 4kk + c of head hn (zeros for the padding heads).
   u32x4 qop[4];
 #pragma unroll
   for (int kk = 0; kk < 4; ++kk) {
     qop[kk] = u32x4{0u, 0u, 0u, 0u};
-    if (hn < it.nh)
+    if (hn < nh)
       qop[kk] = *reinterpret_cast<const u32x4*>(
-          a.q + ((int64_t)it.b * a.n_q_heads + it.h0 + hn) * kHeadDim + 32 * kk + 8 * c);
+          a.q + ((int64_t)b * a.n_q_heads + h0 + hn) * kHeadDim + 32 * kk + 8 * c);
   }
 
   f32x4 acc[8];
@@ -179,25 +172,25 @@ __global__ __launch_bounds__(64) void attn_mfma_kernel(const AttnArgs a) {
   for (int tcol = 0; tcol < 8; ++tcol) acc[tcol] = f32x4{0.f, 0.f, 0.f, 0.f};
   float m = kNegInf, l = 0.f;
 
-  const uint16_t* kbase = a.k_cache + it.strip;
-  const uint16_t* vbase = a.v_cache + it.strip;
-  const int last = it.r1 - 1;
+  const uint16_t* kbase = a.k_cache + strip;
+  const uint16_t* vbase = a.v_cache + strip;
+  const int last = r1 - 1;
 
   TileRegs ta, tb;
-  load_tile(ta, kbase, vbase, a.row_stride, it.r0, last, hn, c);
-  for (int row0 = it.r0; row0 < it.r1; row0 += 64) {
-    const bool has_b = row0 + 32 < it.r1;
+  load_tile(ta, kbase, vbase, a.row_stride, r0, last, hn, c);
+  for (int row0 = r0; row0 < r1; row0 += 64) {
+    const bool has_b = row0 + 32 < r1;
     if (has_b) load_tile(tb, kbase, vbase, a.row_stride, row0 + 32, last, hn, c);
-    process_tile<BF16>(ta, qop, acc, m, l, a.scale_log2e, row0, it.r1, c);
-    if (row0 + 64 < it.r1) load_tile(ta, kbase, vbase, a.row_stride, row0 + 64, last, hn, c);
-    if (has_b) process_tile<BF16>(tb, qop, acc, m, l, a.scale_log2e, row0 + 32, it.r1, c);
+    process_tile<BF16>(ta, qop, acc, m, l, a.scale_log2e, row0, r1, c);
+    if (row0 + 64 < r1) load_tile(ta, kbase, vbase, a.row_stride, row0 + 64, last, hn, c);
+    if (has_b) process_tile<BF16>(tb, qop, acc, m, l, a.scale_log2e, row0 + 32, r1, c);
   }
 
   // The four lanes of a head share m; add up their partial sums.
   l += xor16(l);
   l += xor32(l);
-  if (hn < it.nh) {
-    const int64_t pi = partial_index(a, it, it.h0 + hn);
+  if (hn < nh) {
+    const int64_t pi = ((int64_t)b * a.n_q_heads + h0 + hn) * a.n_chunks + slot;
     float* op = a.ws_o + pi * kHeadDim + 32 * c;
 #pragma unroll
     for (int i = 0; i < 4; ++i) {
@@ -211,6 +204,128 @@ __global__ __launch_bounds__(64) void attn_mfma_kernel(const AttnArgs a) {
       a.ws_m[pi] = m;
       a.ws_l[pi] = l;
     }
+  }
+}
+
+// Marks partial records [slot0, slot1) of heads h0 .. h0+nh-1 of sequence b as empty.
+__device__ __forceinline__ void mark_empty(const AttnArgs& a, int b, int h0, int nh, int slot0,
+                                           int slot1, int lane) {
+  const int n = slot1 - slot0;
+  for (int idx = lane; idx < nh * n; idx += 64) {
+    const int64_t pi = ((int64_t)b * a.n_q_heads + h0 + idx / n) * a.n_chunks + slot0 + idx % n;
+    a.ws_m[pi] = kNegInf;
+    a.ws_l[pi] = 0.f;
+  }
+}
+
+// Fixed split: one wave per (sequence, kv head, head pass, chunk of chunk_rows rows).
+template <bool BF16>
+__global__ __launch_bounds__(64) void attn_mfma_kernel(const AttnArgs a) {
+  const Item it = decode_item(a, blockIdx.x);
+  const int lane = threadIdx.x;
+  if (it.r1 <= it.r0) {
+    mark_empty(a, it.b, it.h0, it.nh, it.chunk, it.chunk + 1, lane);
+    return;
+  }
+  run_strip<BF16>(a, it.b, it.h0, it.nh, it.strip, it.r0, it.r1, it.chunk, lane);
+}
+
+// Balanced split.  All strips (sequence, kv head, head pass) are laid end to end in units of
+// 32-row tiles (a strip without rows counts as one tile) and the total is cut into equal shares,
+// one per wave, so that every wave streams the same number of bytes however ragged the batch is.
+// A share that crosses strip borders yields one partial record per strip it touches; the record
+// index within a strip is the wave's distance from the first wave that touched that strip.  The
+// wave that finishes a strip marks the strip's remaining records empty.
+//
+// Dynamic LDS: (batch + 1) uint32 -- the exclusive prefix of tiles per sequence (all strips of a
+// sequence have the same number of tiles).
+template <bool BF16>
+__global__ __launch_bounds__(256) void attn_mfma_balanced_kernel(const AttnArgs a) {
+  extern __shared__ uint32_t cum[];            // cum[b] = tiles of all strips of sequences < b
+  __shared__ uint32_t part[256];
+  const int tid = threadIdx.x;
+  const int B = a.batch;
+  const uint32_t spb = (uint32_t)(a.n_kv_heads * a.n_pass);   // strips per sequence
+
+  // tiles per strip of each sequence -> cum[b + 1], then an in-place inclusive scan
+  for (int b = tid; b < B; b += 256) {
+    const int slot = a.slot_id[b];
+    int n = a.ctx_len[b];
+    n = n < a.row_limit ? n : a.row_limit;
+    if (slot < 0 || slot >= a.n_slots || n < 0) n = 0;
+    const uint32_t tiles = n > 0 ? (uint32_t)(n + 31) >> 5 : 1u;
+    cum[b + 1] = tiles * spb;
+  }
+  if (tid == 0) cum[0] = 0;
+  __syncthreads();
+  const int per = (B + 255) / 256;
+  const int lo = tid * per, hi = lo + per < B ? lo + per : B;
+  uint32_t sum = 0;
+  for (int b = lo; b < hi; ++b) sum += cum[b + 1];
+  part[tid] = sum;
+  __syncthreads();
+  for (int off = 1; off < 256; off <<= 1) {
+    const uint32_t add = tid >= off ? part[tid - off] : 0u;
+    __syncthreads();
+    part[tid] += add;
+    __syncthreads();
+  }
+  uint32_t run = part[tid] - sum;              // exclusive prefix of this thread's segment
+  for (int b = lo; b < hi; ++b) {
+    run += cum[b + 1];
+    cum[b + 1] = run;
+  }
+  __syncthreads();
+
+  // Everything below is the same for all lanes of a wave: keep it in scalar registers.
+  auto uni = [](uint32_t x) { return (uint32_t)__builtin_amdgcn_readfirstlane((int)x); };
+  const uint32_t total = uni(cum[B]);
+  const int lane = tid & 63;
+  const uint32_t gw = blockIdx.x * 4 + uni(tid >> 6);          // global wave number
+  uint32_t share = (total + a.n_workers - 1) / a.n_workers;    // tiles per wave
+  share = share > (uint32_t)a.min_share ? share : (uint32_t)a.min_share;
+  uint32_t t = gw * share;
+  const uint32_t t_end = t + share < total ? t + share : total;
+  if (t >= total) return;
+
+  // sequence holding tile t: largest b with cum[b] <= t
+  int b = 0;
+  {
+    int hi_b = B;                                              // cum[hi_b] > t always holds
+    while (hi_b - b > 1) {
+      const int mid = (b + hi_b) >> 1;
+      if (uni(cum[mid]) <= t) b = mid; else hi_b = mid;
+    }
+  }
+  while (t < t_end) {
+    while (uni(cum[b + 1]) <= t) ++b;
+    const uint32_t cb = uni(cum[b]);
+    const uint32_t tiles = (uni(cum[b + 1]) - cb) / spb;        // tiles per strip of sequence b
+    const uint32_t rem = t - cb;
+    const uint32_t sib = rem / tiles, lt0 = rem - sib * tiles;  // strip within b, first local tile
+    uint32_t lt1 = lt0 + (t_end - t);
+    lt1 = lt1 < tiles ? lt1 : tiles;
+    const uint32_t strip_t0 = cb + sib * tiles;             // global index of the strip's tile 0
+    const int slot_idx = (int)(gw - strip_t0 / share);
+    const int g = (int)(sib / (uint32_t)a.n_pass), pass = (int)(sib % (uint32_t)a.n_pass);
+    const int h0 = g * a.group + pass * a.heads_per_pass;
+    const int left = a.group - pass * a.heads_per_pass;
+    const int nh = left < a.heads_per_pass ? left : a.heads_per_pass;
+    const int cslot = a.slot_id[b];
+    int n = a.ctx_len[b];
+    n = n < a.row_limit ? n : a.row_limit;
+    const bool valid = cslot >= 0 && cslot < a.n_slots && n > 0;
+    const int r0 = (int)lt0 * 32;
+    int r1 = (int)lt1 * 32;
+    r1 = r1 < n ? r1 : n;
+    int next_slot = slot_idx;
+    if (valid && r0 < r1) {
+      const int64_t strip = (int64_t)cslot * a.slot_stride + (int64_t)g * a.head_stride;
+      run_strip<BF16>(a, b, h0, nh, strip, r0, r1, slot_idx, lane);
+      next_slot = slot_idx + 1;
+    }
+    if (lt1 == tiles) mark_empty(a, b, h0, nh, next_slot, a.n_chunks, lane);
+    t += lt1 - lt0;
   }
 }
 

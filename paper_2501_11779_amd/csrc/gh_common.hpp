@@ -24,7 +24,9 @@ struct AttnArgs {
   int32_t n_slots, row_limit;                     // row_limit = min(capacity, max_ctx_len)
   int32_t chunk_rows, n_chunks;
   int32_t heads_per_pass, n_pass;                 // head sub-groups of one kv head
-  int32_t n_items;                                // B * H_kv * n_pass * n_chunks
+  int32_t n_items;                                // B * H_kv * n_pass * n_chunks (fixed split)
+  int32_t batch;
+  int32_t n_workers, min_share;                   // balanced split: waves, least tiles per wave
   float scale_log2e;                              // scale * log2(e)
 };
 

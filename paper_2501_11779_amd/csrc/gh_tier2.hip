@@ -73,14 +73,39 @@ int auto_chunk_rows(const gh_problem* p) {
 
 struct Plan {
   int kernel, chunk_rows, n_chunks, per_pass, n_pass;
+  bool balanced;            // equal shares of 32-row tiles per wave instead of fixed chunks
+  int n_workers, min_share; // balanced split only
 };
+
+constexpr int kBalancedMaxBatch = 8192;     // prefix of tiles per sequence lives in LDS
+constexpr int kBalancedWavesPerCU = 8;      // resident waves of the MFMA kernel per compute unit
+constexpr int kBalancedMaxRecords = 64;     // partial records per (sequence, head)
 
 Plan make_plan(const gh_problem* p) {
   Plan pl;
   pl.kernel = resolve_kernel(p);
+  head_passes(p, pl.kernel, &pl.per_pass, &pl.n_pass);
+  pl.balanced = false;
+  pl.n_workers = pl.min_share = 0;
+  const int64_t strips = (int64_t)(p->batch > 0 ? p->batch : 1) * p->n_kv_heads * pl.n_pass;
+  const int64_t max_tiles = p->max_ctx_len > 0 ? (p->max_ctx_len + 31) / 32 : 1;
+  if (pl.kernel == GH_KERNEL_MFMA && p->chunk_rows == 0 && p->batch <= kBalancedMaxBatch &&
+      strips * max_tiles < 0x7fffffff) {
+    // Records per head: enough for the longest strip when strips are up to four times the
+    // average length; beyond that the share per wave grows instead (min_share).
+    pl.balanced = true;
+    pl.n_workers = kComputeUnits * kBalancedWavesPerCU;
+    int64_t c = (4 * (int64_t)pl.n_workers + strips - 1) / strips + 1;
+    if (c < 2) c = 2;
+    if (c > kBalancedMaxRecords) c = kBalancedMaxRecords;
+    if (c > max_tiles + 1) c = max_tiles + 1;
+    pl.n_chunks = (int)c;
+    pl.min_share = (int)((max_tiles + pl.n_chunks - 2) / (pl.n_chunks - 1));
+    pl.chunk_rows = 0;
+    return pl;
+  }
   pl.chunk_rows = p->chunk_rows > 0 ? p->chunk_rows : auto_chunk_rows(p);
   pl.n_chunks = p->max_ctx_len > 0 ? (p->max_ctx_len + pl.chunk_rows - 1) / pl.chunk_rows : 1;
-  head_passes(p, pl.kernel, &pl.per_pass, &pl.n_pass);
   return pl;
 }
 
@@ -200,11 +225,21 @@ int32_t gh_decode_attention(const gh_problem* p, const void* q, const void* k_ca
   a.heads_per_pass = pl.per_pass;
   a.n_pass = pl.n_pass;
   a.n_items = (int32_t)items;
+  a.batch = p->batch;
+  a.n_workers = pl.n_workers;
+  a.min_share = pl.min_share;
   a.scale_log2e = p->scale * 1.44269504088896340736f;
 
   hipStream_t s = static_cast<hipStream_t>(hip_stream);
   const bool bf16 = p->dtype == GH_BF16;
-  if (pl.kernel == GH_KERNEL_MFMA) {
+  if (pl.balanced) {
+    const dim3 grid(pl.n_workers / 4), block(256);
+    const size_t lds = (size_t)(p->batch + 1) * sizeof(uint32_t);
+    if (bf16)
+      hipLaunchKernelGGL(gh::attn_mfma_balanced_kernel<true>, grid, block, lds, s, a);
+    else
+      hipLaunchKernelGGL(gh::attn_mfma_balanced_kernel<false>, grid, block, lds, s, a);
+  } else if (pl.kernel == GH_KERNEL_MFMA) {
     const dim3 grid(a.n_items), block(64);
     if (bf16)
       hipLaunchKernelGGL(gh::attn_mfma_kernel<true>, grid, block, 0, s, a);

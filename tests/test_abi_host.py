@@ -102,8 +102,12 @@ def test_chunk_plan_is_consistent(kernel, B, H, Hkv, maxlen):
              max_ctx_len=maxlen, strides=(Hkv * maxlen * 128, maxlen * 128, 128), kernel=kernel)
     rows = G.gh_decode_chunk_rows(p)
     n = G.gh_decode_num_chunks(p)
-    assert rows > 0 and rows % 64 == 0
-    assert n == -(-maxlen // rows) and n >= 1
+    if kernel == G.GH_KERNEL_VALU or (kernel == G.GH_KERNEL_AUTO and H == Hkv):
+        assert rows > 0 and rows % 64 == 0          # fixed split into chunks of `rows` rows
+        assert n == -(-maxlen // rows) and n >= 1
+    else:
+        assert rows == 0                            # balanced split: equal shares per wave
+        assert 2 <= n <= 64
     assert G.gh_decode_workspace_bytes(p) == B * H * n * (128 + 2) * 4
     # a forced chunk size is taken as given
     p.chunk_rows = 128

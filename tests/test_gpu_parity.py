@@ -30,6 +30,7 @@ def run_gpu(inp, chunk_rows=0, kernel=G.GH_KERNEL_AUTO, append=True, status=None
     p = G.problem_from_inputs(inp, chunk_rows=chunk_rows, kernel=kernel)
     w = inp["workload"]
     ws = G.alloc_workspace(p, DEV)
+    ws.fill_(float("nan"))          # a record the kernel forgets to write poisons the output
     out = torch.full((w.batch, w.n_q_heads, w.head_dim), float("nan"), dtype=torch.float32,
                      device=DEV)
     G.decode_step(p, inp, ws, out, dev_status=status, append=append)
@@ -261,6 +262,36 @@ def test_attention_partials_match_oracle_partials(kernel):
                 # (m, l, o) is defined up to the common factor 2^m: compare what is unique
                 assert abs((m[b, h, c] + math.log2(l[b, h, c])) - (mm + math.log2(ll))) < 1e-4
                 assert np.abs(o[b, h, c] / l[b, h, c] - oo / ll).max() < Hh.MAX_ABS_TOL
+
+
+def test_balanced_split_records_cover_each_head_exactly_once():
+    """Library-chosen split: the records of a head are partial results over ranges the test does
+    not know, so compare what is unique: their merged log-sum-exp and the count of live records."""
+    w = small("bal", len(RAGGED), 8, 2, "bf16", 67)
+    inp = W.make_inputs(w, DEV, lengths=RAGGED, n_slots=len(RAGGED) + 1)
+    host = Hh.host_copy(inp)
+    got, p, ws = run_gpu(inp, 0, G.GH_KERNEL_MFMA)
+    assert G.gh_decode_chunk_rows(p) == 0
+    Hh.assert_parity(got, Hh.oracle_step(inp, host), "balanced")
+    po = Hh.oracle_problem(inp)
+    C_ = G.gh_decode_num_chunks(p)
+    B, H, d = len(RAGGED), 8, 128
+    wsn = ws.cpu().numpy()
+    m = wsn[B * H * C_ * d:B * H * C_ * (d + 1)].reshape(B, H, C_)
+    l = wsn[B * H * C_ * (d + 1):B * H * C_ * (d + 2)].reshape(B, H, C_)
+    assert np.all(np.isfinite(l)) and not np.any(np.isnan(m))
+    for b in range(B):
+        n = int(RAGGED[b]) + 1
+        for h in range(H):
+            live = l[b, h] > 0
+            assert live.sum() >= 1
+            assert np.all(m[b, h][~live] == -np.inf)
+            lse = np.log2(np.sum(l[b, h][live].astype(np.float64) *
+                                 np.exp2(m[b, h][live].astype(np.float64) - m[b, h][live].max()))) \
+                + m[b, h][live].max()
+            mm, ll, _ = O.partial(po, host["q"], host["k_cache"], host["v_cache"], host["slot_id"],
+                                  b, h, 0, n)
+            assert abs(lse - (mm + math.log2(ll))) < 1e-4
 
 
 # ------------------------------------------------------------------ full-size workloads, sampled
