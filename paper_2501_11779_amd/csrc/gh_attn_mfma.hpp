@@ -77,13 +77,13 @@ __device__ __forceinline__ void load_tile(TileRegs& t, const uint16_t* kbase, co
     const uint16_t* kp = kbase + (int64_t)row * row_stride + 8 * c;
 #pragma unroll
     for (int kk = 0; kk < 4; ++kk)
-      t.k[T][kk] = *reinterpret_cast<const u32x4*>(kp + 32 * kk);  // d-chunk 4kk + c
+      t.k[T][kk] = stream_load(kp + 32 * kk);  // d-chunk 4kk + c
   }
 #pragma unroll
   for (int e = 0; e < 8; ++e) {
     int row = tile_row0 + 16 * (e >> 2) + 4 * (e & 3) + c;
     row = row < last ? row : last;
-    t.v[e] = *reinterpret_cast<const u32x4*>(vbase + (int64_t)row * row_stride + 8 * hn);
+    t.v[e] = stream_load(vbase + (int64_t)row * row_stride + 8 * hn);
   }
 }
 
@@ -176,14 +176,16 @@ __device__ __forceinline__ void run_strip(const AttnArgs& a, int b, int h0, int 
   const uint16_t* vbase = a.v_cache + strip;
   const int last = r1 - 1;
 
+  // Two register tiles in flight.  The loads are issued unconditionally (rows past the end are
+  // clamped to the last row, whose lines are already in cache) so that the number of outstanding
+  // loads is known at every wait and a tile's arithmetic overlaps the next tile's loads.
   TileRegs ta, tb;
   load_tile(ta, kbase, vbase, a.row_stride, r0, last, hn, c);
   for (int row0 = r0; row0 < r1; row0 += 64) {
-    const bool has_b = row0 + 32 < r1;
-    if (has_b) load_tile(tb, kbase, vbase, a.row_stride, row0 + 32, last, hn, c);
+    load_tile(tb, kbase, vbase, a.row_stride, row0 + 32, last, hn, c);
     process_tile<BF16>(ta, qop, acc, m, l, a.scale_log2e, row0, r1, c);
-    if (row0 + 64 < r1) load_tile(ta, kbase, vbase, a.row_stride, row0 + 64, last, hn, c);
-    if (has_b) process_tile<BF16>(tb, qop, acc, m, l, a.scale_log2e, row0 + 32, r1, c);
+    load_tile(ta, kbase, vbase, a.row_stride, row0 + 64, last, hn, c);
+    if (row0 + 32 < r1) process_tile<BF16>(tb, qop, acc, m, l, a.scale_log2e, row0 + 32, r1, c);
   }
 
   // The four lanes of a head share m; add up their partial sums.
@@ -220,7 +222,7 @@ __device__ __forceinline__ void mark_empty(const AttnArgs& a, int b, int h0, int
 
 // Fixed split: one wave per (sequence, kv head, head pass, chunk of chunk_rows rows).
 template <bool BF16>
-__global__ __launch_bounds__(64) void attn_mfma_kernel(const AttnArgs a) {
+__global__ __launch_bounds__(64, 2) void attn_mfma_kernel(const AttnArgs a) {
   const Item it = decode_item(a, blockIdx.x);
   const int lane = threadIdx.x;
   if (it.r1 <= it.r0) {
@@ -240,7 +242,7 @@ __global__ __launch_bounds__(64) void attn_mfma_kernel(const AttnArgs a) {
 // Dynamic LDS: (batch + 1) uint32 -- the exclusive prefix of tiles per sequence (all strips of a
 // sequence have the same number of tiles).
 template <bool BF16>
-__global__ __launch_bounds__(256) void attn_mfma_balanced_kernel(const AttnArgs a) {
+__global__ __launch_bounds__(256, 2) void attn_mfma_balanced_kernel(const AttnArgs a) {
   extern __shared__ uint32_t cum[];            // cum[b] = tiles of all strips of sequences < b
   __shared__ uint32_t part[256];
   const int tid = threadIdx.x;

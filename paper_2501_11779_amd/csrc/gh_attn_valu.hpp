@@ -70,8 +70,8 @@ __global__ __launch_bounds__(256) void attn_valu_kernel(const AttnArgs a) {
     for (int u = 0; u < UNROLL; ++u) {
       const int row = r + 16 * u;
       const int64_t off = (int64_t)(row < last ? row : last) * a.row_stride;
-      kw[u] = *reinterpret_cast<const uint4*>(kbase + off);
-      vw[u] = *reinterpret_cast<const uint4*>(vbase + off);
+      kw[u] = __builtin_bit_cast(uint4, stream_load(kbase + off));
+      vw[u] = __builtin_bit_cast(uint4, stream_load(vbase + off));
     }
     float s[GT][UNROLL];
 #pragma unroll
