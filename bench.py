@@ -79,6 +79,9 @@ def main():
     ap.add_argument("--batch", type=int, default=0, help="experiment: override the batch size")
     ap.add_argument("--const-len", type=int, default=0,
                     help="experiment: every sequence has this many cached rows")
+    ap.add_argument("--pmc-calibration", action="store_true",
+                    help="also run one plain 1 GiB device copy, the known-size kernel that "
+                         "rocprofv3 FETCH_SIZE / WRITE_SIZE readings are scaled by")
     ap.add_argument("--traffic-bytes", type=float, default=None,
                     help="HBM bytes per attention launch from rocprofv3 counters, if measured")
     args = ap.parse_args()
@@ -135,6 +138,12 @@ def main():
         if events is not None:
             events[2].record()
 
+    if args.pmc_calibration:
+        src = torch.zeros(1 << 30, dtype=torch.uint8, device="cuda")
+        dst = torch.empty_like(src)
+        dst.copy_(src)
+        torch.cuda.synchronize()
+        del src, dst
     for _ in range(args.warmup):
         step()
     torch.cuda.synchronize()
