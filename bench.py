@@ -23,6 +23,11 @@ if ROOT not in sys.path:
 
 HBM_PEAK_GBS = 8000.0   # MI355X published HBM3E peak
 
+# HBM bytes per gh_decode_attention launch (FETCH_SIZE + WRITE_SIZE, each scaled by what the same
+# counter reads for a plain 1 GiB device copy) from the rocprofv3 --pmc runs summarised in
+# profiles/gh_decode_attention_<workload>.md; valid for the library's default kernel and split.
+MEASURED_TRAFFIC_BYTES = {"c2": 1308483095, "c3": 2691279018, "c4": 9224956250, "c5": 2226160831}
+
 CONFIG_OF = {"c1": "configs[0]", "c2": "configs[1]", "c3": "configs[2]", "c4": "configs[3]",
              "c5": "configs[4]"}
 
@@ -184,7 +189,10 @@ def main():
         "roofline": {"bound": "hbm", "kernel": "gh_decode_attention",
                      "achieved": achieved, "peak": HBM_PEAK_GBS, "unit": "GB/s",
                      "frac": achieved / HBM_PEAK_GBS,
-                     "traffic": args.traffic_bytes,
+                     "traffic": args.traffic_bytes if args.traffic_bytes is not None else (
+                         MEASURED_TRAFFIC_BYTES.get(w.name)
+                         if args.kernel == "auto" and not (args.chunk_rows or args.batch or args.const_len)
+                         else None),
                      "algorithmic_bytes_per_launch": attn_bytes,
                      "avg_launch_ms": float(attn_ms.mean())},
     }

@@ -56,9 +56,9 @@ typedef enum { GH_F16 = 0, GH_BF16 = 1 } gh_dtype;
 
 /* Which attention kernel gh_decode_attention launches. */
 typedef enum {
-  GH_KERNEL_AUTO = 0, /* the library's measured choice for the head-group size  */
-  GH_KERNEL_VALU = 1, /* fp32 vector arithmetic, any group size                  */
-  GH_KERNEL_MFMA = 2  /* matrix-core tiles (16 heads per pass)                   */
+  GH_KERNEL_AUTO = 0, /* the library's measured choice (currently always MFMA)   */
+  GH_KERNEL_VALU = 1, /* fp32 vector arithmetic, passes of up to 8 heads          */
+  GH_KERNEL_MFMA = 2  /* matrix-core tiles, passes of up to 16 heads              */
 } gh_kernel;
 
 /* Bits OR-ed into *dev_status by gh_kv_append. */
@@ -77,8 +77,8 @@ typedef struct {
   int64_t head_stride;
   int64_t row_stride;
   float scale;           /* softmax scaling of the scores, e.g. 1/sqrt(head_dim) */
-  int32_t chunk_rows;    /* rows per context chunk; 0 = library picks.  Must be
-                            a positive multiple of 64 otherwise.                 */
+  int32_t chunk_rows;    /* > 0: fixed split, rows per context chunk, a multiple
+                            of 64.  0: the library splits (see below).           */
   int32_t kernel;        /* gh_kernel                                            */
 } gh_problem;
 
@@ -86,21 +86,30 @@ typedef struct {
 const char* gh_status_string(int32_t status);
 
 /*
- * Pure host functions: the split of the context into chunks (footnote of
- * Section 2.2: attention parallelised along the sequence).
- *   gh_decode_chunk_rows  rows per chunk actually used (p->chunk_rows, or the
- *                         library's choice when that is 0); < 0 = gh_status.
- *   gh_decode_num_chunks  C = ceil(max_ctx_len / chunk_rows), at least 1;
+ * Pure host functions: the split of the context (footnote of Section 2.2:
+ * attention parallelised along the sequence).
+ *
+ * Fixed split (chunk_rows > 0, and always for GH_KERNEL_VALU, where 0 lets the
+ * library pick the chunk size): record c of a head covers rows
+ * [c*chunk_rows, (c+1)*chunk_rows) of its sequence.
+ * Balanced split (chunk_rows == 0 with the MFMA kernel, batch <= 8192): the
+ * rows of the whole batch are cut into equal shares, one per resident wave;
+ * the non-empty records of a head cover consecutive row ranges that partition
+ * [0, ctx_len) but whose borders depend on the other sequences' lengths.
+ *
+ *   gh_decode_chunk_rows  rows per chunk of the fixed split, 0 for the
+ *                         balanced split; < 0 = gh_status.
+ *   gh_decode_num_chunks  C = partial records per (sequence, head), >= 1;
  *                         < 0 = gh_status.
  *   gh_decode_workspace_bytes  bytes of workspace the two decode calls need
  *                         (0 if the problem is invalid or batch == 0).
  *
  * Workspace layout (fp32, base 16-byte aligned), with d = head_dim:
  *   o[B][H][C][d]  then  m[B][H][C]  then  l[B][H][C]
- * For chunk c of (sequence b, head h), over the rows r of that chunk and with
+ * For record c of (sequence b, head h), over the rows r it covers and with
  * t_r = scale * log2(e) * (q . K_r):
  *   m = max_r t_r,  l = sum_r 2^(t_r - m),  o[:] = sum_r 2^(t_r - m) * V_r[:]
- * A chunk with no rows has m = -inf, l = 0 and an unspecified o.
+ * A record without rows has m = -inf, l = 0 and an unspecified o.
  */
 int32_t gh_decode_chunk_rows(const gh_problem* p);
 int32_t gh_decode_num_chunks(const gh_problem* p);

@@ -102,7 +102,7 @@ def test_chunk_plan_is_consistent(kernel, B, H, Hkv, maxlen):
              max_ctx_len=maxlen, strides=(Hkv * maxlen * 128, maxlen * 128, 128), kernel=kernel)
     rows = G.gh_decode_chunk_rows(p)
     n = G.gh_decode_num_chunks(p)
-    if kernel == G.GH_KERNEL_VALU or (kernel == G.GH_KERNEL_AUTO and H == Hkv):
+    if kernel == G.GH_KERNEL_VALU:
         assert rows > 0 and rows % 64 == 0          # fixed split into chunks of `rows` rows
         assert n == -(-maxlen // rows) and n >= 1
     else:
