@@ -84,6 +84,8 @@ def main():
     ap.add_argument("--batch", type=int, default=0, help="experiment: override the batch size")
     ap.add_argument("--const-len", type=int, default=0,
                     help="experiment: every sequence has this many cached rows")
+    ap.add_argument("--capacity", type=int, default=0,
+                    help="experiment: rows per cache slot (default: longest context + 1)")
     ap.add_argument("--pmc-calibration", action="store_true",
                     help="also run one plain 1 GiB device copy, the known-size kernel that "
                          "rocprofv3 FETCH_SIZE / WRITE_SIZE readings are scaled by")
@@ -114,7 +116,7 @@ def main():
             lengths=("const", args.const_len) if args.const_len else w.lengths,
             note=w.note + " [EXPERIMENT: overridden batch/lengths]")
     t0 = time.perf_counter()
-    inp = W.make_inputs(w, "cuda")
+    inp = W.make_inputs(w, "cuda", capacity=args.capacity or None)
     torch.cuda.synchronize()
     kernel = {"auto": G.GH_KERNEL_AUTO, "valu": G.GH_KERNEL_VALU, "mfma": G.GH_KERNEL_MFMA}[args.kernel]
     p = G.problem_from_inputs(inp, chunk_rows=args.chunk_rows, kernel=kernel)
@@ -191,7 +193,7 @@ def main():
                      "frac": achieved / HBM_PEAK_GBS,
                      "traffic": args.traffic_bytes if args.traffic_bytes is not None else (
                          MEASURED_TRAFFIC_BYTES.get(w.name)
-                         if args.kernel == "auto" and not (args.chunk_rows or args.batch or args.const_len)
+                         if args.kernel == "auto" and not (args.chunk_rows or args.batch or args.const_len or args.capacity)
                          else None),
                      "algorithmic_bytes_per_launch": attn_bytes,
                      "avg_launch_ms": float(attn_ms.mean())},

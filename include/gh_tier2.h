@@ -92,7 +92,7 @@ const char* gh_status_string(int32_t status);
  * Fixed split (chunk_rows > 0, and always for GH_KERNEL_VALU, where 0 lets the
  * library pick the chunk size): record c of a head covers rows
  * [c*chunk_rows, (c+1)*chunk_rows) of its sequence.
- * Balanced split (chunk_rows == 0 with the MFMA kernel, batch <= 8192): the
+ * Balanced split (chunk_rows == 0 with the MFMA kernel, batch <= 4096): the
  * rows of the whole batch are cut into equal shares, one per resident wave;
  * the non-empty records of a head cover consecutive row ranges that partition
  * [0, ctx_len) but whose borders depend on the other sequences' lengths.
@@ -104,12 +104,14 @@ const char* gh_status_string(int32_t status);
  *   gh_decode_workspace_bytes  bytes of workspace the two decode calls need
  *                         (0 if the problem is invalid or batch == 0).
  *
- * Workspace layout (fp32, base 16-byte aligned), with d = head_dim:
- *   o[B][H][C][d]  then  m[B][H][C]  then  l[B][H][C]
+ * Workspace layout (base 16-byte aligned), with d = head_dim:
+ *   float o[B][H][C][d], float m[B][H][C], float l[B][H][C], int32 n[B][H]
+ * n = how many of a head's C records are in use (records at index >= n are
+ * unspecified and ignored by the merge).
  * For record c of (sequence b, head h), over the rows r it covers and with
  * t_r = scale * log2(e) * (q . K_r):
  *   m = max_r t_r,  l = sum_r 2^(t_r - m),  o[:] = sum_r 2^(t_r - m) * V_r[:]
- * A record without rows has m = -inf, l = 0 and an unspecified o.
+ * A record in use that covers no rows has m = -inf, l = 0, unspecified o.
  */
 int32_t gh_decode_chunk_rows(const gh_problem* p);
 int32_t gh_decode_num_chunks(const gh_problem* p);
@@ -133,8 +135,8 @@ int32_t gh_kv_append(const gh_problem* p, void* k_cache, void* v_cache,
  * Split-context attention (Table 5's Q.K and A.V, fused, softmax kept as a
  * running max and sum in fp32).  q: [B, H, d] contiguous.  ctx_len[b] = rows
  * attended for sequence b (pos[b] + 1 after an append); rows at or beyond it
- * are never read.  Writes every (m, l) of the workspace and the o of every
- * non-empty chunk.  A sequence with ctx_len <= 0 or a slot id out of range
+ * are never read.  Writes n for every head, (m, l) of every record in use and
+ * the o of every non-empty one.  A sequence with ctx_len <= 0 or a slot id out of range
  * produces only empty chunks.  ctx_len above min(max_ctx_len, slot_capacity)
  * is clamped to it.
  */
@@ -145,8 +147,8 @@ int32_t gh_decode_attention(const gh_problem* p, const void* q,
                             void* hip_stream);
 
 /*
- * Merge of the chunk partials (same footnote).  Per (b, h), over the chunks
- * with l > 0:  M = max_c m_c,
+ * Merge of the chunk partials (same footnote).  Per (b, h), over the records
+ * in use with l > 0:  M = max_c m_c,
  *   out[b][h][:] = sum_c 2^(m_c - M) * o_c[:] / sum_c 2^(m_c - M) * l_c
  * and zeros when every chunk is empty.  out: fp32 [B, H, d] contiguous.
  * Deterministic: fixed summation order, no atomics.  ctx_len may be null (it

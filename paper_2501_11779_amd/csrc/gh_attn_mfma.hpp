@@ -186,6 +186,23 @@ __device__ __forceinline__ void process_tile(const TileRegs& t, const u32x4 (&qo
   }
 }
 
+// Loads the Q operand of heads h0 .. h0+nh-1 of sequence b.  Padding lanes (hn >= nh) load head
+// h0 as well -- the load is unconditional so that nothing has to wait for it at the point of
+// issue -- and are zeroed by keep_real_heads() when the operand is taken into use.
+__device__ __forceinline__ void load_q(u32x4 (&qop)[4], const AttnArgs& a, int b, int h0, int nh,
+                                       int hn, int c) {
+  const int head = h0 + (hn < nh ? hn : 0);
+#pragma unroll
+  for (int kk = 0; kk < 4; ++kk)
+    qop[kk] = *reinterpret_cast<const u32x4*>(
+        a.q + ((int64_t)b * a.n_q_heads + head) * kHeadDim + 32 * kk + 8 * c);
+}
+__device__ __forceinline__ void keep_real_heads(u32x4 (&dst)[4], const u32x4 (&src)[4], int nh,
+                                                int hn) {
+#pragma unroll
+  for (int kk = 0; kk < 4; ++kk) dst[kk] = hn < nh ? src[kk] : u32x4{0u, 0u, 0u, 0u};
+}
+
 // Rows [r0, r1) (r0 < r1) of one strip for the heads h0 .. h0+nh-1 of sequence b, written as
 // partial record `slot` of those heads.
 template <bool BF16>
@@ -194,14 +211,9 @@ __device__ __forceinline__ void run_strip(const AttnArgs& a, int b, int h0, int 
   const int hn = lane & 15, c = lane >> 4;
 
   // Q operand: d-chunk 4kk + c of head hn (zeros for the padding heads).
-  u32x4 qop[4];
-#pragma unroll
-  for (int kk = 0; kk < 4; ++kk) {
-    qop[kk] = u32x4{0u, 0u, 0u, 0u};
-    if (hn < nh)
-      qop[kk] = *reinterpret_cast<const u32x4*>(
-          a.q + ((int64_t)b * a.n_q_heads + h0 + hn) * kHeadDim + 32 * kk + 8 * c);
-  }
+  u32x4 qraw[4], qop[4];
+  load_q(qraw, a, b, h0, nh, hn, c);
+  keep_real_heads(qop, qraw, nh, hn);
 
   f32x4 acc[8];
 #pragma unroll
@@ -261,6 +273,8 @@ template <bool BF16>
 __global__ __launch_bounds__(64, 2) void attn_mfma_kernel(const AttnArgs a) {
   const Item it = decode_item(a, blockIdx.x);
   const int lane = threadIdx.x;
+  if (it.chunk == 0 && lane < it.nh)            // every record of a head is written in this split
+    a.ws_n[(int64_t)it.b * a.n_q_heads + it.h0 + lane] = a.n_chunks;
   if (it.r1 <= it.r0) {
     mark_empty(a, it.b, it.h0, it.nh, it.chunk, it.chunk + 1, lane);
     return;
@@ -268,31 +282,74 @@ __global__ __launch_bounds__(64, 2) void attn_mfma_kernel(const AttnArgs a) {
   run_strip<BF16>(a, it.b, it.h0, it.nh, it.strip, it.r0, it.r1, it.chunk, lane);
 }
 
+// Writes the running state as partial record `slot` of heads h0 .. h0+nh-1 of sequence b.
+__device__ __forceinline__ void store_record(const AttnArgs& a, int b, int h0, int nh, int slot,
+                                             const f32x4 (&acc)[8], float m, float l, int hn, int c) {
+  l += xor16(l);                       // the four lanes of a head share m; add their partial sums
+  l += xor32(l);
+  if (hn < nh) {
+    const int64_t pi = ((int64_t)b * a.n_q_heads + h0 + hn) * a.n_chunks + slot;
+    float* op = a.ws_o + pi * kHeadDim + 32 * c;
+#pragma unroll
+    for (int i = 0; i < 4; ++i) {
+      // register i of column tile t is column 32c + 8i + t
+      const float4 x0 = make_float4(acc[0][i], acc[1][i], acc[2][i], acc[3][i]);
+      const float4 x1 = make_float4(acc[4][i], acc[5][i], acc[6][i], acc[7][i]);
+      *reinterpret_cast<float4*>(op + 8 * i) = x0;
+      *reinterpret_cast<float4*>(op + 8 * i + 4) = x1;
+    }
+    if (c == 0) {
+      a.ws_m[pi] = m;
+      a.ws_l[pi] = l;
+    }
+  }
+}
+
 // Balanced split.  All strips (sequence, kv head, head pass) are laid end to end in units of
 // 32-row tiles (a strip without rows counts as one tile) and the total is cut into equal shares,
 // one per wave, so that every wave streams the same number of bytes however ragged the batch is.
 // A share that crosses strip borders yields one partial record per strip it touches; the record
 // index within a strip is the wave's distance from the first wave that touched that strip.  The
-// wave that finishes a strip marks the strip's remaining records empty.
+// wave that finishes a strip writes the number of records the strip's heads use.
 //
-// Dynamic LDS: (batch + 1) uint32 -- the exclusive prefix of tiles per sequence (all strips of a
-// sequence have the same number of tiles).
+// A wave walks its share as one continuous stream of tiles: the loads of the next tile are in
+// flight while a tile is computed, across strip borders too, and the Q operand of the following
+// strip is fetched one strip ahead.  (Draining the stream at every strip border cost about 20 us
+// per border under load -- three dependent memory round trips.)
+//
+// Dynamic LDS, three arrays indexed by sequence: cum[B + 1] = tiles of all strips of earlier
+// sequences (all strips of a sequence have the same number of tiles), rows[B] = rows attended
+// (0 for a sequence that is skipped), base[B] = slot id (0 for a skipped sequence).
+struct TileCursor {
+  uint32_t t;       // global tile index
+  int b;            // sequence
+  uint32_t sib;     // strip within the sequence: kv head * n_pass + pass
+  uint32_t lt;      // tile within the strip
+  uint32_t tiles;   // tiles per strip of this sequence (>= 1)
+  int n;            // rows attended of this sequence
+  int slot;         // cache slot (0 when n == 0)
+};
+
 template <bool BF16>
 __global__ __launch_bounds__(256, 2) void attn_mfma_balanced_kernel(const AttnArgs a) {
-  extern __shared__ uint32_t cum[];            // cum[b] = tiles of all strips of sequences < b
+  extern __shared__ uint32_t lds[];
   __shared__ uint32_t part[256];
   const int tid = threadIdx.x;
   const int B = a.batch;
+  uint32_t* cum = lds;                                        // [B + 1]
+  int* rows = reinterpret_cast<int*>(lds + B + 1);            // [B]
+  int* slots = rows + B;                                      // [B]
   const uint32_t spb = (uint32_t)(a.n_kv_heads * a.n_pass);   // strips per sequence
 
-  // tiles per strip of each sequence -> cum[b + 1], then an in-place inclusive scan
   for (int b = tid; b < B; b += 256) {
-    const int slot = a.slot_id[b];
+    int slot = a.slot_id[b];
     int n = a.ctx_len[b];
     n = n < a.row_limit ? n : a.row_limit;
     if (slot < 0 || slot >= a.n_slots || n < 0) n = 0;
-    const uint32_t tiles = n > 0 ? (uint32_t)(n + 31) >> 5 : 1u;
-    cum[b + 1] = tiles * spb;
+    if (n == 0) slot = 0;
+    rows[b] = n;
+    slots[b] = slot;
+    cum[b + 1] = (n > 0 ? (uint32_t)(n + 31) >> 5 : 1u) * spb;
   }
   if (tid == 0) cum[0] = 0;
   __syncthreads();
@@ -319,51 +376,143 @@ __global__ __launch_bounds__(256, 2) void attn_mfma_balanced_kernel(const AttnAr
   auto uni = [](uint32_t x) { return (uint32_t)__builtin_amdgcn_readfirstlane((int)x); };
   const uint32_t total = uni(cum[B]);
   const int lane = tid & 63;
+  const int hn = lane & 15, c = lane >> 4;
   const uint32_t gw = blockIdx.x * 4 + uni(tid >> 6);          // global wave number
   uint32_t share = (total + a.n_workers - 1) / a.n_workers;    // tiles per wave
   share = share > (uint32_t)a.min_share ? share : (uint32_t)a.min_share;
-  uint32_t t = gw * share;
-  const uint32_t t_end = t + share < total ? t + share : total;
-  if (t >= total) return;
+  const uint32_t t0 = gw * share;
+  const uint32_t t_end = t0 + share < total ? t0 + share : total;
+  if (t0 >= total) return;
 
-  // sequence holding tile t: largest b with cum[b] <= t
-  int b = 0;
+  auto enter_sequence = [&](TileCursor& cu) {
+    const uint32_t cb = uni(cum[cu.b]);
+    cu.tiles = (uni(cum[cu.b + 1]) - cb) / spb;
+    cu.n = (int)uni((uint32_t)rows[cu.b]);
+    cu.slot = (int)uni((uint32_t)slots[cu.b]);
+  };
+  auto advance = [&](TileCursor& cu) {                         // caller keeps cu.t + 1 < total
+    ++cu.t;
+    if (++cu.lt == cu.tiles) {
+      cu.lt = 0;
+      if (++cu.sib == spb) {
+        cu.sib = 0;
+        ++cu.b;
+        enter_sequence(cu);
+      }
+    }
+  };
+  auto heads_of = [&](uint32_t sib, int& h0, int& nh) {
+    const int g = (int)(sib / (uint32_t)a.n_pass), pass = (int)(sib % (uint32_t)a.n_pass);
+    h0 = g * a.group + pass * a.heads_per_pass;
+    const int left = a.group - pass * a.heads_per_pass;
+    nh = left < a.heads_per_pass ? left : a.heads_per_pass;
+  };
+  auto issue = [&](TileRegs& regs, const TileCursor& cu) {
+    const int g = (int)(cu.sib / (uint32_t)a.n_pass);
+    const int64_t strip = (int64_t)cu.slot * a.slot_stride + (int64_t)g * a.head_stride;
+    load_tile(regs, a.k_cache + strip, a.v_cache + strip, a.row_stride, (int)cu.lt * 32,
+              cu.n > 0 ? cu.n - 1 : 0, hn, c);
+  };
+
+  // cursor of the tile being computed; start: largest b with cum[b] <= t0
+  TileCursor cp;
+  cp.t = t0;
+  cp.b = 0;
   {
-    int hi_b = B;                                              // cum[hi_b] > t always holds
-    while (hi_b - b > 1) {
-      const int mid = (b + hi_b) >> 1;
-      if (uni(cum[mid]) <= t) b = mid; else hi_b = mid;
+    int hi_b = B;                                              // cum[hi_b] > t0 always holds
+    while (hi_b - cp.b > 1) {
+      const int mid = (cp.b + hi_b) >> 1;
+      if (uni(cum[mid]) <= t0) cp.b = mid; else hi_b = mid;
     }
   }
-  while (t < t_end) {
-    while (uni(cum[b + 1]) <= t) ++b;
-    const uint32_t cb = uni(cum[b]);
-    const uint32_t tiles = (uni(cum[b + 1]) - cb) / spb;        // tiles per strip of sequence b
-    const uint32_t rem = t - cb;
-    const uint32_t sib = rem / tiles, lt0 = rem - sib * tiles;  // strip within b, first local tile
-    uint32_t lt1 = lt0 + (t_end - t);
-    lt1 = lt1 < tiles ? lt1 : tiles;
-    const uint32_t strip_t0 = cb + sib * tiles;             // global index of the strip's tile 0
-    const int slot_idx = (int)(gw - strip_t0 / share);
-    const int g = (int)(sib / (uint32_t)a.n_pass), pass = (int)(sib % (uint32_t)a.n_pass);
-    const int h0 = g * a.group + pass * a.heads_per_pass;
-    const int left = a.group - pass * a.heads_per_pass;
-    const int nh = left < a.heads_per_pass ? left : a.heads_per_pass;
-    const int cslot = a.slot_id[b];
-    int n = a.ctx_len[b];
-    n = n < a.row_limit ? n : a.row_limit;
-    const bool valid = cslot >= 0 && cslot < a.n_slots && n > 0;
-    const int r0 = (int)lt0 * 32;
-    int r1 = (int)lt1 * 32;
-    r1 = r1 < n ? r1 : n;
-    int next_slot = slot_idx;
-    if (valid && r0 < r1) {
-      const int64_t strip = (int64_t)cslot * a.slot_stride + (int64_t)g * a.head_stride;
-      run_strip<BF16>(a, b, h0, nh, strip, r0, r1, slot_idx, lane);
-      next_slot = slot_idx + 1;
+  enter_sequence(cp);
+  {
+    const uint32_t rem = t0 - uni(cum[cp.b]);
+    cp.sib = rem / cp.tiles;
+    cp.lt = rem - cp.sib * cp.tiles;
+  }
+  TileCursor ld = cp;                                          // cursor of the next tile to load
+  // cursor of the strip whose Q operand is fetched next (first tile of a strip, or past the end)
+  TileCursor qs = cp;
+  auto next_strip = [&](TileCursor& cu) {                      // cu.t becomes >= t_end when done
+    cu.t += cu.tiles - cu.lt;
+    cu.lt = 0;
+    if (cu.t < t_end) {
+      if (++cu.sib == spb) {
+        cu.sib = 0;
+        ++cu.b;
+        enter_sequence(cu);
+      }
     }
-    if (lt1 == tiles) mark_empty(a, b, h0, nh, next_slot, a.n_chunks, lane);
-    t += lt1 - lt0;
+  };
+
+  // qop: operand of the strip being computed; qnext: raw rows of the following strip, in flight
+  // for a whole strip before they are taken into use; qnext_nh: how many of its heads are real.
+  u32x4 qop[4], qnext[4];
+  int h0, nh, qnext_nh = 0;
+  heads_of(cp.sib, h0, nh);
+  load_q(qnext, a, cp.b, h0, nh, hn, c);
+  keep_real_heads(qop, qnext, nh, hn);
+  next_strip(qs);
+  if (qs.t < t_end) {
+    int qh0;
+    heads_of(qs.sib, qh0, qnext_nh);
+    load_q(qnext, a, qs.b, qh0, qnext_nh, hn, c);
+  }
+
+  f32x4 acc[8];
+#pragma unroll
+  for (int tcol = 0; tcol < 8; ++tcol) acc[tcol] = f32x4{0.f, 0.f, 0.f, 0.f};
+  float m = kNegInf, l = 0.f;
+
+  // One tile of arithmetic; closes the record when the tile ends this wave's piece of the strip.
+  auto compute = [&](const TileRegs& regs) {
+    if (cp.n > 0)
+      process_tile<BF16>(regs, qop, acc, m, l, a.scale_log2e, (int)cp.lt * 32, cp.n, c);
+    const bool strip_end = cp.lt + 1 == cp.tiles;
+    if (strip_end || cp.t + 1 == t_end) {
+      const uint32_t strip_t0 = cp.t - cp.lt;                  // global index of the strip's tile 0
+      int rec = (int)(gw - strip_t0 / share);
+      heads_of(cp.sib, h0, nh);
+      if (cp.n > 0) {
+        store_record(a, cp.b, h0, nh, rec, acc, m, l, hn, c);
+        ++rec;
+      }
+      if (strip_end && hn < nh && c == 0)                     // records in use for these heads
+        a.ws_n[(int64_t)cp.b * a.n_q_heads + h0 + hn] = rec;
+      if (cp.t + 1 < t_end) {                                  // the next tile opens a strip
+#pragma unroll
+        for (int tcol = 0; tcol < 8; ++tcol) acc[tcol] = f32x4{0.f, 0.f, 0.f, 0.f};
+        m = kNegInf;
+        l = 0.f;
+        keep_real_heads(qop, qnext, qnext_nh, hn);
+        next_strip(qs);
+        {
+          // unconditional: when no strip follows, this strip's rows are fetched again (unused)
+          const bool more = qs.t < t_end;
+          int qh0;
+          heads_of(more ? qs.sib : cp.sib, qh0, qnext_nh);
+          load_q(qnext, a, more ? qs.b : cp.b, qh0, qnext_nh, hn, c);
+        }
+      }
+    }
+  };
+
+  // Two register tiles.  Loads are issued unconditionally (past the end of the share the last
+  // position is loaded again, from cache) so that every wait count is exact.
+  TileRegs ta, tb;
+  issue(ta, ld);
+  while (true) {
+    if (ld.t + 1 < t_end) advance(ld);
+    issue(tb, ld);
+    compute(ta);
+    if (cp.t + 1 >= t_end) break;
+    advance(cp);
+    if (ld.t + 1 < t_end) advance(ld);
+    issue(ta, ld);
+    compute(tb);
+    if (cp.t + 1 >= t_end) break;
+    advance(cp);
   }
 }
 

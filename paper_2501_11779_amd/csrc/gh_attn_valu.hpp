@@ -22,6 +22,8 @@ __global__ __launch_bounds__(256) void attn_valu_kernel(const AttnArgs a) {
 
   const Item it = decode_item(a, blockIdx.x);
   const int tid = threadIdx.x;
+  if (it.chunk == 0 && tid < it.nh)          // every record of a head is written in this split
+    a.ws_n[(int64_t)it.b * a.n_q_heads + it.h0 + tid] = a.n_chunks;
   if (it.r1 <= it.r0) {                      // empty chunk: flag it and leave
     if (tid < it.nh) {
       const int64_t pi = partial_index(a, it, it.h0 + tid);

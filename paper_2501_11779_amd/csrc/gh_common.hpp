@@ -19,6 +19,7 @@ struct AttnArgs {
   float* ws_o;              // [B, H, C, 128]
   float* ws_m;              // [B, H, C]
   float* ws_l;              // [B, H, C]
+  int32_t* ws_n;            // [B, H]  records in use per head
   int64_t slot_stride, head_stride, row_stride;   // elements
   int32_t n_q_heads, n_kv_heads, group;           // H, H_kv, G = H / H_kv
   int32_t n_slots, row_limit;                     // row_limit = min(capacity, max_ctx_len)

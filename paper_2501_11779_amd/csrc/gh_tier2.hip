@@ -77,7 +77,7 @@ struct Plan {
   int n_workers, min_share; // balanced split only
 };
 
-constexpr int kBalancedMaxBatch = 8192;     // prefix of tiles per sequence lives in LDS
+constexpr int kBalancedMaxBatch = 4096;     // three per-sequence arrays live in LDS (48 KB)
 constexpr int kBalancedWavesPerCU = 8;      // resident waves of the MFMA kernel per compute unit
 constexpr int kBalancedMaxRecords = 64;     // partial records per (sequence, head)
 
@@ -110,7 +110,7 @@ Plan make_plan(const gh_problem* p) {
 }
 
 size_t workspace_floats(const gh_problem* p, const Plan& pl) {
-  return (size_t)p->batch * p->n_q_heads * pl.n_chunks * (gh::kHeadDim + 2);
+  return (size_t)p->batch * p->n_q_heads * ((size_t)pl.n_chunks * (gh::kHeadDim + 2) + 1);
 }
 
 template <bool BF16>
@@ -212,6 +212,7 @@ int32_t gh_decode_attention(const gh_problem* p, const void* q, const void* k_ca
   a.ws_o = static_cast<float*>(workspace);
   a.ws_m = a.ws_o + nrec * gh::kHeadDim;
   a.ws_l = a.ws_m + nrec;
+  a.ws_n = reinterpret_cast<int32_t*>(a.ws_l + nrec);
   a.slot_stride = p->slot_stride;
   a.head_stride = p->head_stride;
   a.row_stride = p->row_stride;
@@ -234,7 +235,7 @@ int32_t gh_decode_attention(const gh_problem* p, const void* q, const void* k_ca
   const bool bf16 = p->dtype == GH_BF16;
   if (pl.balanced) {
     const dim3 grid(pl.n_workers / 4), block(256);
-    const size_t lds = (size_t)(p->batch + 1) * sizeof(uint32_t);
+    const size_t lds = (size_t)(3 * p->batch + 1) * sizeof(uint32_t);
     if (bf16)
       hipLaunchKernelGGL(gh::attn_mfma_balanced_kernel<true>, grid, block, lds, s, a);
     else
@@ -268,6 +269,7 @@ int32_t gh_decode_reduce(const gh_problem* p, const void* workspace, const int32
   a.ws_o = static_cast<const float*>(workspace);
   a.ws_m = a.ws_o + nrec * gh::kHeadDim;
   a.ws_l = a.ws_m + nrec;
+  a.ws_n = reinterpret_cast<const int32_t*>(a.ws_l + nrec);
   a.out = out;
   a.n_rows = (int64_t)p->batch * p->n_q_heads;
   a.n_chunks = pl.n_chunks;

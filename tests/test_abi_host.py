@@ -108,7 +108,7 @@ def test_chunk_plan_is_consistent(kernel, B, H, Hkv, maxlen):
     else:
         assert rows == 0                            # balanced split: equal shares per wave
         assert 2 <= n <= 64
-    assert G.gh_decode_workspace_bytes(p) == B * H * n * (128 + 2) * 4
+    assert G.gh_decode_workspace_bytes(p) == B * H * (n * (128 + 2) + 1) * 4
     # a forced chunk size is taken as given
     p.chunk_rows = 128
     assert G.gh_decode_chunk_rows(p) == 128

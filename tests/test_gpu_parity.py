@@ -225,7 +225,9 @@ def test_reduce_matches_oracle_merge_of_oracle_partials():
                 mm, ll, oo = O.partial(po, host["q"], host["k_cache"], host["v_cache"],
                                        host["slot_id"], b, h, r0, r1)
                 m[b, h, c], l[b, h, c], o[b, h, c] = mm, ll, oo
-    ws = torch.from_numpy(np.concatenate([o.ravel(), m.ravel(), l.ravel()])).to(DEV)
+    used = np.full((B, H), C_, dtype=np.int32)          # every record of every head is in use
+    ws = torch.from_numpy(np.concatenate([o.ravel(), m.ravel(), l.ravel(),
+                                          used.ravel().view(np.float32)])).to(DEV)
     out = torch.empty((B, H, d), dtype=torch.float32, device=DEV)
     G.check(G.gh_decode_reduce(p, ws, None, out))
     torch.cuda.synchronize()
@@ -279,13 +281,13 @@ def test_balanced_split_records_cover_each_head_exactly_once():
     wsn = ws.cpu().numpy()
     m = wsn[B * H * C_ * d:B * H * C_ * (d + 1)].reshape(B, H, C_)
     l = wsn[B * H * C_ * (d + 1):B * H * C_ * (d + 2)].reshape(B, H, C_)
-    assert np.all(np.isfinite(l)) and not np.any(np.isnan(m))
+    used = wsn[B * H * C_ * (d + 2):B * H * C_ * (d + 2) + B * H].view(np.int32).reshape(B, H)
+    assert used.min() >= 1 and used.max() <= C_
     for b in range(B):
         n = int(RAGGED[b]) + 1
         for h in range(H):
-            live = l[b, h] > 0
-            assert live.sum() >= 1
-            assert np.all(m[b, h][~live] == -np.inf)
+            live = np.arange(C_) < used[b, h]
+            assert np.all(np.isfinite(l[b, h][live])) and np.all(l[b, h][live] > 0)
             lse = np.log2(np.sum(l[b, h][live].astype(np.float64) *
                                  np.exp2(m[b, h][live].astype(np.float64) - m[b, h][live].max()))) \
                 + m[b, h][live].max()
