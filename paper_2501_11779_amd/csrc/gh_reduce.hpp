@@ -14,31 +14,72 @@ struct ReduceArgs {
   int32_t n_chunks;
 };
 
-// One wave per (sequence, head); a lane owns two adjacent columns.  Chunks are
-// visited in index order, so the result does not depend on scheduling.
+__device__ __forceinline__ float wave_max(float x) {
+#pragma unroll
+  for (int off = 32; off >= 1; off >>= 1) x = fmaxf(x, __shfl_xor(x, off, 64));
+  return x;
+}
+
+// One wave per (sequence, head); a lane owns two adjacent columns.  The (m, l) of the records
+// are read 64 at a time, one per lane, to find the common maximum and the weights; the o rows
+// are then accumulated in record order with independent loads, so the result does not depend on
+// scheduling.
 __global__ __launch_bounds__(256) void decode_reduce_kernel(const ReduceArgs a) {
   const int lane = threadIdx.x & 63;
   const int64_t row = (int64_t)blockIdx.x * 4 + (threadIdx.x >> 6);
   if (row >= a.n_rows) return;
+  int used = a.ws_n[row];
+  used = used < 0 ? 0 : used < a.n_chunks ? used : a.n_chunks;
   const float* m = a.ws_m + row * a.n_chunks;
   const float* l = a.ws_l + row * a.n_chunks;
   const float* o = a.ws_o + row * a.n_chunks * kHeadDim + 2 * lane;
-  int used = a.ws_n[row];
-  used = used < 0 ? 0 : used < a.n_chunks ? used : a.n_chunks;
+
   float M = kNegInf;
-  for (int c = 0; c < used; ++c)
-    if (l[c] > 0.f) M = fmaxf(M, m[c]);
+  for (int c0 = 0; c0 < used; c0 += 64) {
+    const int c = c0 + lane;
+    const float lc = c < used ? l[c] : 0.f;
+    const float mc = c < used ? m[c] : kNegInf;
+    M = fmaxf(M, lc > 0.f ? mc : kNegInf);     // a record without rows carries no maximum
+  }
+  M = wave_max(M);
+
   float2 acc = make_float2(0.f, 0.f);
   float L = 0.f;
   if (M != kNegInf) {
-    for (int c = 0; c < used; ++c) {
-      const float lc = l[c];
-      if (!(lc > 0.f)) continue;                     // empty chunk: its o is unspecified
-      const float w = fast_exp2(m[c] - M);
-      const float2 oc = *reinterpret_cast<const float2*>(o + (int64_t)c * kHeadDim);
-      acc.x = fmaf(w, oc.x, acc.x);
-      acc.y = fmaf(w, oc.y, acc.y);
-      L = fmaf(w, lc, L);
+    for (int c0 = 0; c0 < used; c0 += 64) {
+      const int c = c0 + lane;
+      const float lc = c < used ? l[c] : 0.f;
+      const float mc = c < used ? m[c] : kNegInf;
+      const float w = lc > 0.f ? fast_exp2(mc - M) : 0.f;   // this lane's record weight
+      const float wl = w * lc;
+      const int n = used - c0 < 64 ? used - c0 : 64;
+      int j = 0;
+      for (; j + 4 <= n; j += 4) {                           // four independent row loads
+        float2 oc[4];
+        float wj[4];
+#pragma unroll
+        for (int u = 0; u < 4; ++u) {
+          wj[u] = __shfl(w, j + u, 64);
+          oc[u] = *reinterpret_cast<const float2*>(o + (int64_t)(c0 + j + u) * kHeadDim);
+        }
+#pragma unroll
+        for (int u = 0; u < 4; ++u) {
+          if (wj[u] > 0.f) {                                 // an empty record's o is unspecified
+            acc.x = fmaf(wj[u], oc[u].x, acc.x);
+            acc.y = fmaf(wj[u], oc[u].y, acc.y);
+          }
+          L += __shfl(wl, j + u, 64);
+        }
+      }
+      for (; j < n; ++j) {
+        const float wj = __shfl(w, j, 64);
+        const float2 oc = *reinterpret_cast<const float2*>(o + (int64_t)(c0 + j) * kHeadDim);
+        if (wj > 0.f) {
+          acc.x = fmaf(wj, oc.x, acc.x);
+          acc.y = fmaf(wj, oc.y, acc.y);
+        }
+        L += __shfl(wl, j, 64);
+      }
     }
     acc.x /= L;
     acc.y /= L;

@@ -100,6 +100,28 @@ def test_attention_matches_oracle_on_ragged_batch(kernel, dtype, H, Hkv, chunk_r
 
 
 @pytest.mark.parametrize("kernel", ["valu", "mfma"])
+def test_more_than_64_records_per_head(kernel):
+    """Fixed split with 64-row chunks over 4300 rows: 68 records per head, merged 64 at a time."""
+    w = small("many", 3, 4, 2, "bf16", 51)
+    inp = W.make_inputs(w, DEV, lengths=np.array([4300, 90, 4160], dtype=np.int32))
+    host = Hh.host_copy(inp)
+    got, p, _ = run_gpu(inp, 64, KERNELS[kernel])
+    assert G.gh_decode_num_chunks(p) == 68
+    Hh.assert_parity(got, Hh.oracle_step(inp, host), "68 records")
+
+
+def test_batch_above_the_balanced_split_limit_uses_the_fixed_split():
+    """More than 4096 sequences: the library falls back to fixed chunks for the MFMA kernel."""
+    B = 4100
+    w = W.Workload("big", B, 4, 2, 128, "f16", ("uniform", 0, 150), 52)
+    inp = W.make_inputs(w, DEV)
+    host = Hh.host_copy(inp)
+    got, p, _ = run_gpu(inp, 0, G.GH_KERNEL_MFMA)
+    assert G.gh_decode_chunk_rows(p) > 0
+    Hh.assert_parity(got, Hh.oracle_step(inp, host), "B=4100")
+
+
+@pytest.mark.parametrize("kernel", ["valu", "mfma"])
 def test_token_major_layout(kernel):
     w = small("tok", 6, 8, 2, "bf16", 50)
     L = np.array([5, 64, 100, 257, 31, 400], dtype=np.int32)
