@@ -86,6 +86,11 @@ def main():
                     help="experiment: every sequence has this many cached rows")
     ap.add_argument("--capacity", type=int, default=0,
                     help="experiment: rows per cache slot (default: longest context + 1)")
+    ap.add_argument("--paged", action="store_true",
+                    help="keep the caches in a gh_slot_pool (virtual slots, pages mapped on demand)")
+    ap.add_argument("--page-rows", type=int, default=1024)
+    ap.add_argument("--virtual-capacity", type=int, default=0,
+                    help="rows per virtual slot in --paged mode (default: 3x the mean context)")
     ap.add_argument("--pmc-calibration", action="store_true",
                     help="also run one plain 1 GiB device copy, the known-size kernel that "
                          "rocprofv3 FETCH_SIZE / WRITE_SIZE readings are scaled by")
@@ -116,8 +121,27 @@ def main():
             lengths=("const", args.const_len) if args.const_len else w.lengths,
             note=w.note + " [EXPERIMENT: overridden batch/lengths]")
     t0 = time.perf_counter()
-    inp = W.make_inputs(w, "cuda", capacity=args.capacity or None)
+    inp = W.make_inputs(w, "cuda", capacity=args.capacity or None,
+                        layout="token_major" if args.paged else "head_major")
     torch.cuda.synchronize()
+    pool = None
+    paged_info = None
+    cpu = None
+    if args.paged:
+        if not args.no_cpu_baseline:
+            cpu = cpu_baseline(inp)          # needs the generated tensors, which the pool replaces
+        from paper_2501_11779_amd.paged import into_pool, pages_needed
+        need = pages_needed(inp["lengths"], args.page_rows)
+        vcap = args.virtual_capacity or max(int(inp["lengths"].max()) + 1,
+                                            int(3 * need * args.page_rows / w.batch))
+        pool = G.SlotPool(inp["n_slots"], vcap, w.n_kv_heads, w.head_dim, args.page_rows, need)
+        inp = into_pool(pool, inp, poison=False)
+        st = pool.stats()
+        paged_info = {"page_rows": args.page_rows, "page_bytes": st.page_bytes,
+                      "virtual_GB": st.virtual_bytes / 1e9, "physical_GB": st.physical_bytes / 1e9,
+                      "oversubscription": st.virtual_bytes / st.physical_bytes,
+                      "layout": "token-major, HIP virtual memory"}
+        log(f"paged slots: {paged_info}")
     kernel = {"auto": G.GH_KERNEL_AUTO, "valu": G.GH_KERNEL_VALU, "mfma": G.GH_KERNEL_MFMA}[args.kernel]
     p = G.problem_from_inputs(inp, chunk_rows=args.chunk_rows, kernel=kernel)
     ws = G.alloc_workspace(p)
@@ -186,6 +210,7 @@ def main():
                                f"seed={w.seed}",
                    "kernel": args.kernel, "chunk_rows": chunk_rows, "n_chunks": n_chunks,
                    "step": "gh_kv_append + gh_decode_attention + gh_decode_reduce",
+                   "paged_slots": paged_info,
                    "step_algorithmic_bytes": step_bytes,
                    "step_GBps": step_bytes / (elapsed / args.steps) / 1e9},
         "roofline": {"bound": "hbm", "kernel": "gh_decode_attention",
@@ -193,13 +218,13 @@ def main():
                      "frac": achieved / HBM_PEAK_GBS,
                      "traffic": args.traffic_bytes if args.traffic_bytes is not None else (
                          MEASURED_TRAFFIC_BYTES.get(w.name)
-                         if args.kernel == "auto" and not (args.chunk_rows or args.batch or args.const_len or args.capacity)
+                         if args.kernel == "auto" and not (args.chunk_rows or args.batch or args.const_len or args.capacity or args.paged)
                          else None),
                      "algorithmic_bytes_per_launch": attn_bytes,
                      "avg_launch_ms": float(attn_ms.mean())},
     }
     if not args.no_cpu_baseline:
-        result["cpu_baseline"] = cpu_baseline(inp)
+        result["cpu_baseline"] = cpu if cpu is not None else cpu_baseline(inp)
         log(f"cpu_baseline: {result['cpu_baseline']}")
     print(json.dumps(result), flush=True)
 

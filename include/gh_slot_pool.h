@@ -1,0 +1,99 @@
+/*
+ * gh_slot_pool.h -- context slots that are virtually contiguous and physically
+ * paged on demand (host-side C ABI, one MI355X).
+ *
+ * The paper's context memory is a fixed set of KV-cache slots per Tier-2 node
+ * (Section 4.1.3: the Dispatcher hands out slot ids, slots are reused without
+ * being released), stored with paging over a virtual address range so that the
+ * slots can be oversubscribed about 3x (Section 4.3: virtual memory management
+ * used to implement paged attention; Appendix C: context memory of a node is
+ * oversubscribed because few prompts reach the maximum length).  This pool is
+ * the HIP counterpart: it reserves a virtual range for n_slots * capacity rows
+ * of K and of V, owns a fixed budget of physical pages, and maps pages under a
+ * slot as the slot's sequence grows.  The kernels of gh_tier2.h run unchanged
+ * on the pool's base pointers: they never touch a row at or beyond ctx_len.
+ *
+ * Layout: token-major, element (slot s, row r, kv head g, column j) at
+ *   s*slot_stride + r*row_stride + g*head_stride + j        (elements)
+ * with row_stride = n_kv_heads*head_dim, head_stride = head_dim and
+ * slot_stride = capacity*row_stride, capacity rounded up to whole pages.  A
+ * page holds page_rows consecutive rows of all kv heads of one slot.
+ *
+ * Every function here is a HOST function working on HOST arguments; slot ids
+ * and row counts are host arrays (the controller knows each prompt's position).
+ * Mapping and unmapping are synchronous driver calls.  The caller must not
+ * launch work that touches rows it has not reserved, and must let work on a
+ * slot finish before releasing it.  Not thread-safe.
+ */
+#ifndef GH_SLOT_POOL_H
+#define GH_SLOT_POOL_H
+
+#include <stddef.h>
+#include <stdint.h>
+
+#ifdef __cplusplus
+extern "C" {
+#endif
+
+typedef struct gh_slot_pool gh_slot_pool;
+
+typedef struct {
+  int32_t n_slots;        /* slots in the virtual range                               */
+  int32_t slot_capacity;  /* rows per slot wanted; rounded up to a multiple of page_rows */
+  int32_t n_kv_heads;
+  int32_t head_dim;       /* 128                                                      */
+  int32_t page_rows;      /* rows per page; page bytes = page_rows*n_kv_heads*head_dim*2
+                             must be a multiple of the driver's mapping granularity   */
+  int32_t device;         /* HIP device ordinal                                       */
+  int64_t physical_pages; /* budget: pages of K (and as many of V) that exist at all  */
+} gh_slot_pool_config;
+
+typedef struct {
+  int64_t page_bytes;       /* bytes of one page of one cache                         */
+  int64_t virtual_bytes;    /* reserved address range, K plus V                       */
+  int64_t physical_bytes;   /* physical memory owned, K plus V                        */
+  int64_t pages_total;      /* physical_pages                                         */
+  int64_t pages_mapped;     /* pages currently under some slot                        */
+  int32_t slot_capacity;    /* rows per slot after rounding                           */
+  int32_t slots_in_use;     /* slots with at least one page                           */
+} gh_slot_pool_stats;
+
+/* Status codes are those of gh_tier2.h: 0 ok, -1 null, -2 shape, -3 unsupported
+ * (page size not a multiple of the mapping granularity), -5 capacity (the
+ * physical budget or a slot's capacity is exceeded), -6 the HIP runtime failed. */
+
+/* Reserves the address range and creates the physical pages (nothing mapped yet). */
+int32_t gh_slot_pool_create(const gh_slot_pool_config* cfg, gh_slot_pool** out);
+
+/* Unmaps and frees everything.  Work using the pool must have finished. */
+int32_t gh_slot_pool_destroy(gh_slot_pool* pool);
+
+/* Device base pointers of the K and V ranges, and the (slot, head, row) strides
+ * in elements in the order gh_problem wants them. */
+void* gh_slot_pool_k(const gh_slot_pool* pool);
+void* gh_slot_pool_v(const gh_slot_pool* pool);
+int32_t gh_slot_pool_strides(const gh_slot_pool* pool, int64_t* slot_stride,
+                             int64_t* head_stride, int64_t* row_stride);
+
+/*
+ * Makes sure rows [0, rows[i]) of slot slot_id[i] are backed by pages, for
+ * i < count.  All or nothing: if the free pages do not cover the whole request,
+ * or a row count exceeds the slot capacity, or a slot id is out of range,
+ * nothing is mapped and -5 / -2 is returned.  Pages already mapped stay.
+ */
+int32_t gh_slot_pool_reserve(gh_slot_pool* pool, const int32_t* slot_id,
+                             const int32_t* rows, int32_t count);
+
+/* Returns every page of the listed slots to the free list (slot reuse by a new
+ * prompt needs no release: the rows are simply overwritten). */
+int32_t gh_slot_pool_release(gh_slot_pool* pool, const int32_t* slot_id, int32_t count);
+
+/* Rows of a slot that are currently backed by pages (0 for a bad slot id). */
+int32_t gh_slot_pool_mapped_rows(const gh_slot_pool* pool, int32_t slot);
+
+int32_t gh_slot_pool_get_stats(const gh_slot_pool* pool, gh_slot_pool_stats* out);
+
+#ifdef __cplusplus
+}
+#endif
+#endif /* GH_SLOT_POOL_H */

@@ -22,6 +22,9 @@ GH_DEV_BAD_SLOT, GH_DEV_BAD_POS = 1, 2
 
 EXPORTS = ("gh_status_string", "gh_decode_chunk_rows", "gh_decode_num_chunks",
            "gh_decode_workspace_bytes", "gh_kv_append", "gh_decode_attention", "gh_decode_reduce")
+POOL_EXPORTS = ("gh_slot_pool_create", "gh_slot_pool_destroy", "gh_slot_pool_k", "gh_slot_pool_v",
+                "gh_slot_pool_strides", "gh_slot_pool_reserve", "gh_slot_pool_release",
+                "gh_slot_pool_mapped_rows", "gh_slot_pool_get_stats")
 
 
 class gh_problem(C.Structure):
@@ -31,6 +34,22 @@ class gh_problem(C.Structure):
         ("slot_capacity", C.c_int32), ("max_ctx_len", C.c_int32),
         ("slot_stride", C.c_int64), ("head_stride", C.c_int64), ("row_stride", C.c_int64),
         ("scale", C.c_float), ("chunk_rows", C.c_int32), ("kernel", C.c_int32),
+    ]
+
+
+class gh_slot_pool_config(C.Structure):
+    _fields_ = [
+        ("n_slots", C.c_int32), ("slot_capacity", C.c_int32), ("n_kv_heads", C.c_int32),
+        ("head_dim", C.c_int32), ("page_rows", C.c_int32), ("device", C.c_int32),
+        ("physical_pages", C.c_int64),
+    ]
+
+
+class gh_slot_pool_stats(C.Structure):
+    _fields_ = [
+        ("page_bytes", C.c_int64), ("virtual_bytes", C.c_int64), ("physical_bytes", C.c_int64),
+        ("pages_total", C.c_int64), ("pages_mapped", C.c_int64),
+        ("slot_capacity", C.c_int32), ("slots_in_use", C.c_int32),
     ]
 
 
@@ -67,6 +86,26 @@ def lib():
         L.gh_decode_attention.argtypes = [P, V, V, V, V, V, V, C.c_size_t, V]
         L.gh_decode_reduce.restype = C.c_int32
         L.gh_decode_reduce.argtypes = [P, V, V, V, V]
+        I32P = C.POINTER(C.c_int32)
+        I64P = C.POINTER(C.c_int64)
+        L.gh_slot_pool_create.restype = C.c_int32
+        L.gh_slot_pool_create.argtypes = [C.POINTER(gh_slot_pool_config), C.POINTER(V)]
+        L.gh_slot_pool_destroy.restype = C.c_int32
+        L.gh_slot_pool_destroy.argtypes = [V]
+        L.gh_slot_pool_k.restype = V
+        L.gh_slot_pool_k.argtypes = [V]
+        L.gh_slot_pool_v.restype = V
+        L.gh_slot_pool_v.argtypes = [V]
+        L.gh_slot_pool_strides.restype = C.c_int32
+        L.gh_slot_pool_strides.argtypes = [V, I64P, I64P, I64P]
+        L.gh_slot_pool_reserve.restype = C.c_int32
+        L.gh_slot_pool_reserve.argtypes = [V, I32P, I32P, C.c_int32]
+        L.gh_slot_pool_release.restype = C.c_int32
+        L.gh_slot_pool_release.argtypes = [V, I32P, C.c_int32]
+        L.gh_slot_pool_mapped_rows.restype = C.c_int32
+        L.gh_slot_pool_mapped_rows.argtypes = [V, C.c_int32]
+        L.gh_slot_pool_get_stats.restype = C.c_int32
+        L.gh_slot_pool_get_stats.argtypes = [V, C.POINTER(gh_slot_pool_stats)]
         _lib = L
     return _lib
 
@@ -159,3 +198,82 @@ def decode_step(p, inp, workspace, out, dev_status=None, stream=None, append=Tru
                               inp["ctx_len"], workspace, None, stream))
     check(gh_decode_reduce(p, workspace, inp["ctx_len"], out, stream))
     return out
+
+
+# ----------------------------------------------------------------------------- paged context slots
+def _i32_array(values):
+    arr = (C.c_int32 * len(values))(*[int(v) for v in values])
+    return arr, len(values)
+
+
+class _DeviceArrayView:
+    """Lets torch wrap a raw device address (no copy, no ownership)."""
+
+    def __init__(self, ptr, shape):
+        self.__cuda_array_interface__ = {"shape": tuple(shape), "typestr": "<i2", "data": (ptr, False),
+                                         "version": 2}
+
+
+class SlotPool:
+    """Marshalling front end of gh_slot_pool_* (include/gh_slot_pool.h)."""
+
+    def __init__(self, n_slots, slot_capacity, n_kv_heads, head_dim, page_rows, physical_pages,
+                 device=0):
+        self._h = C.c_void_p()
+        cfg = gh_slot_pool_config(n_slots, slot_capacity, n_kv_heads, head_dim, page_rows, device,
+                                  physical_pages)
+        check(lib().gh_slot_pool_create(C.byref(cfg), C.byref(self._h)))
+        self.n_slots, self.n_kv_heads, self.head_dim = n_slots, n_kv_heads, head_dim
+        self.page_rows = page_rows
+        self.capacity = self.stats().slot_capacity
+
+    def close(self):
+        if self._h:
+            h, self._h = self._h, C.c_void_p()
+            check(lib().gh_slot_pool_destroy(h))
+
+    def __del__(self):
+        try:
+            self.close()
+        except Exception:
+            pass
+
+    @property
+    def k_ptr(self):
+        return lib().gh_slot_pool_k(self._h)
+
+    @property
+    def v_ptr(self):
+        return lib().gh_slot_pool_v(self._h)
+
+    @property
+    def strides(self):
+        a, b, c = C.c_int64(), C.c_int64(), C.c_int64()
+        check(lib().gh_slot_pool_strides(self._h, C.byref(a), C.byref(b), C.byref(c)))
+        return (a.value, b.value, c.value)
+
+    def reserve(self, slot_ids, rows):
+        s, n = _i32_array(slot_ids)
+        r, _ = _i32_array(rows)
+        return lib().gh_slot_pool_reserve(self._h, s, r, n)
+
+    def release(self, slot_ids):
+        s, n = _i32_array(slot_ids)
+        return lib().gh_slot_pool_release(self._h, s, n)
+
+    def mapped_rows(self, slot):
+        return lib().gh_slot_pool_mapped_rows(self._h, int(slot))
+
+    def stats(self):
+        st = gh_slot_pool_stats()
+        check(lib().gh_slot_pool_get_stats(self._h, C.byref(st)))
+        return st
+
+    def rows_view(self, which, slot, rows, dtype):
+        """Torch view [rows, H_kv, d] of the first `rows` rows of a slot; they must be reserved."""
+        assert 0 <= rows <= self.mapped_rows(slot)
+        base = self.k_ptr if which == "k" else self.v_ptr
+        ptr = base + slot * self.strides[0] * 2
+        view = torch.as_tensor(_DeviceArrayView(ptr, (rows, self.n_kv_heads, self.head_dim)),
+                               device="cuda")
+        return view.view(dtype)

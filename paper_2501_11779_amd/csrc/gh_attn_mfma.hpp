@@ -410,8 +410,11 @@ __global__ __launch_bounds__(256, 2) void attn_mfma_balanced_kernel(const AttnAr
   auto issue = [&](TileRegs& regs, const TileCursor& cu) {
     const int g = (int)(cu.sib / (uint32_t)a.n_pass);
     const int64_t strip = (int64_t)cu.slot * a.slot_stride + (int64_t)g * a.head_stride;
-    load_tile(regs, a.k_cache + strip, a.v_cache + strip, a.row_stride, (int)cu.lt * 32,
-              cu.n > 0 ? cu.n - 1 : 0, hn, c);
+    // A strip without rows reads the first 256 bytes of q instead: the loads stay unconditional,
+    // and no cache address is touched that the caller did not declare attended (a paged cache
+    // may have nothing mapped there).
+    load_tile(regs, cu.n > 0 ? a.k_cache + strip : a.q, cu.n > 0 ? a.v_cache + strip : a.q,
+              a.row_stride, (int)cu.lt * 32, cu.n > 0 ? cu.n - 1 : 0, hn, c);
   };
 
   // cursor of the tile being computed; start: largest b with cum[b] <= t0

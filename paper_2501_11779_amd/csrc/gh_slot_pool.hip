@@ -1,0 +1,229 @@
+// Context slots backed by HIP virtual memory management: a virtual range per cache, a fixed
+// budget of physical pages, pages mapped under a slot as its sequence grows.
+// Contract: include/gh_slot_pool.h.
+#include "gh_slot_pool.h"
+
+#include <hip/hip_runtime.h>
+
+#include <new>
+#include <vector>
+
+namespace {
+constexpr int32_t kOk = 0, kNull = -1, kShape = -2, kUnsupported = -3, kCapacity = -5, kHip = -6;
+}
+
+struct gh_slot_pool {
+  gh_slot_pool_config cfg;
+  int32_t capacity = 0;            // rows per slot, whole pages
+  int32_t pages_per_slot = 0;
+  size_t page_bytes = 0, slot_bytes = 0, range_bytes = 0;
+  char* k_va = nullptr;
+  char* v_va = nullptr;
+  std::vector<hipMemGenericAllocationHandle_t> k_pages, v_pages;   // physical pages
+  std::vector<int32_t> free_list;                                  // ids of unmapped pages
+  std::vector<std::vector<int32_t>> slot_pages;                    // per slot, in row order
+  int64_t mapped = 0;
+};
+
+namespace {
+
+bool map_page(gh_slot_pool* p, int32_t slot, int32_t index, int32_t page) {
+  const size_t off = (size_t)slot * p->slot_bytes + (size_t)index * p->page_bytes;
+  hipMemAccessDesc acc = {};
+  acc.location.type = hipMemLocationTypeDevice;
+  acc.location.id = p->cfg.device;
+  acc.flags = hipMemAccessFlagsProtReadWrite;
+  if (hipMemMap(p->k_va + off, p->page_bytes, 0, p->k_pages[page], 0) != hipSuccess) return false;
+  if (hipMemMap(p->v_va + off, p->page_bytes, 0, p->v_pages[page], 0) != hipSuccess) {
+    (void)hipMemUnmap(p->k_va + off, p->page_bytes);
+    return false;
+  }
+  if (hipMemSetAccess(p->k_va + off, p->page_bytes, &acc, 1) != hipSuccess ||
+      hipMemSetAccess(p->v_va + off, p->page_bytes, &acc, 1) != hipSuccess) {
+    (void)hipMemUnmap(p->k_va + off, p->page_bytes);
+    (void)hipMemUnmap(p->v_va + off, p->page_bytes);
+    return false;
+  }
+  return true;
+}
+
+bool unmap_page(gh_slot_pool* p, int32_t slot, int32_t index) {
+  const size_t off = (size_t)slot * p->slot_bytes + (size_t)index * p->page_bytes;
+  const bool a = hipMemUnmap(p->k_va + off, p->page_bytes) == hipSuccess;
+  const bool b = hipMemUnmap(p->v_va + off, p->page_bytes) == hipSuccess;
+  return a && b;
+}
+
+}  // namespace
+
+extern "C" {
+
+int32_t gh_slot_pool_create(const gh_slot_pool_config* cfg, gh_slot_pool** out) {
+  if (!cfg || !out) return kNull;
+  *out = nullptr;
+  if (cfg->n_slots <= 0 || cfg->slot_capacity <= 0 || cfg->n_kv_heads <= 0 || cfg->page_rows <= 0 ||
+      cfg->physical_pages <= 0 || cfg->device < 0)
+    return kShape;
+  if (cfg->head_dim != 128) return kUnsupported;
+  int n_dev = 0;
+  if (hipGetDeviceCount(&n_dev) != hipSuccess || cfg->device >= n_dev) return kHip;
+  if (hipSetDevice(cfg->device) != hipSuccess) return kHip;
+  int vmm = 0;
+  if (hipDeviceGetAttribute(&vmm, hipDeviceAttributeVirtualMemoryManagementSupported, cfg->device) !=
+          hipSuccess || !vmm)
+    return kUnsupported;
+
+  hipMemAllocationProp prop = {};
+  prop.type = hipMemAllocationTypePinned;
+  prop.location.type = hipMemLocationTypeDevice;
+  prop.location.id = cfg->device;
+  size_t gran = 0;
+  if (hipMemGetAllocationGranularity(&gran, &prop, hipMemAllocationGranularityMinimum) != hipSuccess ||
+      gran == 0)
+    return kHip;
+
+  gh_slot_pool* p = new (std::nothrow) gh_slot_pool();
+  if (!p) return kHip;
+  p->cfg = *cfg;
+  p->page_bytes = (size_t)cfg->page_rows * cfg->n_kv_heads * cfg->head_dim * 2;
+  if (p->page_bytes % gran != 0) {
+    delete p;
+    return kUnsupported;
+  }
+  p->pages_per_slot = (cfg->slot_capacity + cfg->page_rows - 1) / cfg->page_rows;
+  p->capacity = p->pages_per_slot * cfg->page_rows;
+  p->slot_bytes = (size_t)p->pages_per_slot * p->page_bytes;
+  p->range_bytes = (size_t)cfg->n_slots * p->slot_bytes;
+
+  void* kv = nullptr;
+  void* vv = nullptr;
+  if (hipMemAddressReserve(&kv, p->range_bytes, gran, nullptr, 0) != hipSuccess) {
+    delete p;
+    return kHip;
+  }
+  if (hipMemAddressReserve(&vv, p->range_bytes, gran, nullptr, 0) != hipSuccess) {
+    (void)hipMemAddressFree(kv, p->range_bytes);
+    delete p;
+    return kHip;
+  }
+  p->k_va = static_cast<char*>(kv);
+  p->v_va = static_cast<char*>(vv);
+  p->slot_pages.resize(cfg->n_slots);
+  bool ok = true;
+  for (int64_t i = 0; i < cfg->physical_pages && ok; ++i) {
+    hipMemGenericAllocationHandle_t hk, hv;
+    if (hipMemCreate(&hk, p->page_bytes, &prop, 0) != hipSuccess) {
+      ok = false;
+      break;
+    }
+    if (hipMemCreate(&hv, p->page_bytes, &prop, 0) != hipSuccess) {
+      (void)hipMemRelease(hk);
+      ok = false;
+      break;
+    }
+    p->k_pages.push_back(hk);
+    p->v_pages.push_back(hv);
+  }
+  if (!ok) {
+    gh_slot_pool_destroy(p);
+    return kHip;
+  }
+  p->free_list.reserve(p->k_pages.size());
+  for (int64_t i = (int64_t)p->k_pages.size() - 1; i >= 0; --i) p->free_list.push_back((int32_t)i);
+  *out = p;
+  return kOk;
+}
+
+int32_t gh_slot_pool_destroy(gh_slot_pool* p) {
+  if (!p) return kNull;
+  bool ok = true;
+  for (int32_t s = 0; s < (int32_t)p->slot_pages.size(); ++s)
+    for (int32_t i = 0; i < (int32_t)p->slot_pages[s].size(); ++i) ok = unmap_page(p, s, i) && ok;
+  for (auto h : p->k_pages) ok = hipMemRelease(h) == hipSuccess && ok;
+  for (auto h : p->v_pages) ok = hipMemRelease(h) == hipSuccess && ok;
+  if (p->k_va) ok = hipMemAddressFree(p->k_va, p->range_bytes) == hipSuccess && ok;
+  if (p->v_va) ok = hipMemAddressFree(p->v_va, p->range_bytes) == hipSuccess && ok;
+  delete p;
+  return ok ? kOk : kHip;
+}
+
+void* gh_slot_pool_k(const gh_slot_pool* p) { return p ? p->k_va : nullptr; }
+void* gh_slot_pool_v(const gh_slot_pool* p) { return p ? p->v_va : nullptr; }
+
+int32_t gh_slot_pool_strides(const gh_slot_pool* p, int64_t* slot_stride, int64_t* head_stride,
+                             int64_t* row_stride) {
+  if (!p || !slot_stride || !head_stride || !row_stride) return kNull;
+  *row_stride = (int64_t)p->cfg.n_kv_heads * p->cfg.head_dim;
+  *head_stride = p->cfg.head_dim;
+  *slot_stride = (int64_t)p->capacity * *row_stride;
+  return kOk;
+}
+
+int32_t gh_slot_pool_reserve(gh_slot_pool* p, const int32_t* slot_id, const int32_t* rows,
+                             int32_t count) {
+  if (!p || (count > 0 && (!slot_id || !rows))) return kNull;
+  if (count < 0) return kShape;
+  // First pass: is the whole request satisfiable?  (A slot listed twice counts its larger need.)
+  std::vector<int32_t> want(p->slot_pages.size(), 0);
+  for (int32_t i = 0; i < count; ++i) {
+    if (slot_id[i] < 0 || slot_id[i] >= p->cfg.n_slots || rows[i] < 0) return kShape;
+    if (rows[i] > p->capacity) return kCapacity;
+    const int32_t need = (rows[i] + p->cfg.page_rows - 1) / p->cfg.page_rows;
+    if (need > want[slot_id[i]]) want[slot_id[i]] = need;
+  }
+  int64_t extra = 0;
+  for (size_t s = 0; s < want.size(); ++s) {
+    const int32_t have = (int32_t)p->slot_pages[s].size();
+    if (want[s] > have) extra += want[s] - have;
+  }
+  if (extra > (int64_t)p->free_list.size()) return kCapacity;
+  for (size_t s = 0; s < want.size(); ++s) {
+    while ((int32_t)p->slot_pages[s].size() < want[s]) {
+      const int32_t page = p->free_list.back();
+      if (!map_page(p, (int32_t)s, (int32_t)p->slot_pages[s].size(), page)) return kHip;
+      p->free_list.pop_back();
+      p->slot_pages[s].push_back(page);
+      ++p->mapped;
+    }
+  }
+  return kOk;
+}
+
+int32_t gh_slot_pool_release(gh_slot_pool* p, const int32_t* slot_id, int32_t count) {
+  if (!p || (count > 0 && !slot_id)) return kNull;
+  if (count < 0) return kShape;
+  for (int32_t i = 0; i < count; ++i)
+    if (slot_id[i] < 0 || slot_id[i] >= p->cfg.n_slots) return kShape;
+  bool ok = true;
+  for (int32_t i = 0; i < count; ++i) {
+    auto& pages = p->slot_pages[slot_id[i]];
+    while (!pages.empty()) {
+      ok = unmap_page(p, slot_id[i], (int32_t)pages.size() - 1) && ok;
+      p->free_list.push_back(pages.back());
+      pages.pop_back();
+      --p->mapped;
+    }
+  }
+  return ok ? kOk : kHip;
+}
+
+int32_t gh_slot_pool_mapped_rows(const gh_slot_pool* p, int32_t slot) {
+  if (!p || slot < 0 || slot >= p->cfg.n_slots) return 0;
+  return (int32_t)p->slot_pages[slot].size() * p->cfg.page_rows;
+}
+
+int32_t gh_slot_pool_get_stats(const gh_slot_pool* p, gh_slot_pool_stats* out) {
+  if (!p || !out) return kNull;
+  out->page_bytes = (int64_t)p->page_bytes;
+  out->virtual_bytes = 2 * (int64_t)p->range_bytes;
+  out->physical_bytes = 2 * (int64_t)p->k_pages.size() * (int64_t)p->page_bytes;
+  out->pages_total = (int64_t)p->k_pages.size();
+  out->pages_mapped = p->mapped;
+  out->slot_capacity = p->capacity;
+  int32_t used = 0;
+  for (const auto& s : p->slot_pages) used += s.empty() ? 0 : 1;
+  out->slots_in_use = used;
+  return kOk;
+}
+
+}  // extern "C"

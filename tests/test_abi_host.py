@@ -10,8 +10,8 @@ from paper_2501_11779_amd import binding as G
 ROOT = os.path.dirname(os.path.dirname(os.path.abspath(__file__)))
 
 
-def _declared_functions():
-    text = open(os.path.join(ROOT, "include", "gh_tier2.h")).read()
+def _declared_functions(header="gh_tier2.h"):
+    text = open(os.path.join(ROOT, "include", header)).read()
     text = re.sub(r"/\*.*?\*/", "", text, flags=re.S)
     return sorted(set(re.findall(r"\b(gh_[a-z_0-9]+)\s*\(", text)))
 
@@ -30,6 +30,23 @@ def test_library_loads_and_exports_every_declared_symbol():
     L = G.lib()
     for n in names:
         assert getattr(L, n) is not None
+
+
+def test_slot_pool_symbols_are_exported_and_arguments_checked_without_a_gpu():
+    names = _declared_functions("gh_slot_pool.h")
+    assert set(names) == set(G.POOL_EXPORTS)
+    L = G.lib()
+    for n in names:
+        assert getattr(L, n) is not None
+    handle = C.c_void_p()
+    assert L.gh_slot_pool_create(None, C.byref(handle)) == G.GH_ERR_NULL
+    cfg = G.gh_slot_pool_config(0, 100, 2, 128, 256, 0, 4)
+    assert L.gh_slot_pool_create(C.byref(cfg), C.byref(handle)) == G.GH_ERR_SHAPE
+    cfg = G.gh_slot_pool_config(4, 100, 2, 64, 256, 0, 4)
+    assert L.gh_slot_pool_create(C.byref(cfg), C.byref(handle)) == G.GH_ERR_UNSUPPORTED
+    assert L.gh_slot_pool_destroy(None) == G.GH_ERR_NULL
+    assert L.gh_slot_pool_k(None) is None and L.gh_slot_pool_mapped_rows(None, 0) == 0
+    assert L.gh_slot_pool_reserve(None, None, None, 0) == G.GH_ERR_NULL
 
 
 def test_status_strings():
