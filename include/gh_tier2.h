@@ -25,6 +25,9 @@
  *     `head_dim` elements of one row are contiguous.  K and V are separate
  *     allocations with the same geometry.
  *   - Query head h reads kv head h / (n_q_heads / n_kv_heads).
+ *   - A cache that holds several layers (a Tier-1 node hosts a range of
+ *     layers, Section 4.1.2) is addressed by passing the layer's base pointer:
+ *     slots are then indexed by (layer, sequence) with no other change.
  *   - Host-checkable mistakes return a negative gh_status and launch
  *     nothing.  Conditions only visible on the device (slot id or position
  *     out of range) make the kernel skip that sequence and OR a bit into
@@ -80,6 +83,13 @@ typedef struct {
   int32_t chunk_rows;    /* > 0: fixed split, rows per context chunk, a multiple
                             of 64.  0: the library splits (see below).           */
   int32_t kernel;        /* gh_kernel                                            */
+  int64_t q_batch_stride;   /* elements between the query rows of consecutive
+                               sequences; 0 = contiguous [B, H, d] (H*d)          */
+  int64_t new_batch_stride; /* the same for k_new and v_new; 0 = contiguous
+                               [B, H_kv, d] (H_kv*d).  Multiples of 8.  With both
+                               set to (H + 2*H_kv)*d the three inputs can be read
+                               straight out of one packed per-sequence message
+                               q | k | v (Section 5.4.3: what Tier 1 sends).      */
 } gh_problem;
 
 /* Static text for a status code (host pointer, never null). */
@@ -156,6 +166,15 @@ int32_t gh_decode_attention(const gh_problem* p, const void* q,
  */
 int32_t gh_decode_reduce(const gh_problem* p, const void* workspace,
                          const int32_t* ctx_len, float* out, void* hip_stream);
+
+/*
+ * The same merge with the result stored in the model's 16-bit type (p->dtype),
+ * as the paper's kernels store it (Section 4.3) and as Tier 2 sends it back
+ * (2*D bytes per token, Section 5.4.3).  out16: [B, H, d] contiguous, 16-byte
+ * aligned.  The fp32 result is rounded to nearest even once, at the store.
+ */
+int32_t gh_decode_reduce_native(const gh_problem* p, const void* workspace,
+                                const int32_t* ctx_len, void* out16, void* hip_stream);
 
 #ifdef __cplusplus
 }

@@ -21,7 +21,8 @@ GH_KERNEL_AUTO, GH_KERNEL_VALU, GH_KERNEL_MFMA = 0, 1, 2
 GH_DEV_BAD_SLOT, GH_DEV_BAD_POS = 1, 2
 
 EXPORTS = ("gh_status_string", "gh_decode_chunk_rows", "gh_decode_num_chunks",
-           "gh_decode_workspace_bytes", "gh_kv_append", "gh_decode_attention", "gh_decode_reduce")
+           "gh_decode_workspace_bytes", "gh_kv_append", "gh_decode_attention", "gh_decode_reduce",
+           "gh_decode_reduce_native")
 POOL_EXPORTS = ("gh_slot_pool_create", "gh_slot_pool_destroy", "gh_slot_pool_k", "gh_slot_pool_v",
                 "gh_slot_pool_strides", "gh_slot_pool_reserve", "gh_slot_pool_release",
                 "gh_slot_pool_mapped_rows", "gh_slot_pool_get_stats")
@@ -34,6 +35,7 @@ class gh_problem(C.Structure):
         ("slot_capacity", C.c_int32), ("max_ctx_len", C.c_int32),
         ("slot_stride", C.c_int64), ("head_stride", C.c_int64), ("row_stride", C.c_int64),
         ("scale", C.c_float), ("chunk_rows", C.c_int32), ("kernel", C.c_int32),
+        ("q_batch_stride", C.c_int64), ("new_batch_stride", C.c_int64),
     ]
 
 
@@ -86,6 +88,8 @@ def lib():
         L.gh_decode_attention.argtypes = [P, V, V, V, V, V, V, C.c_size_t, V]
         L.gh_decode_reduce.restype = C.c_int32
         L.gh_decode_reduce.argtypes = [P, V, V, V, V]
+        L.gh_decode_reduce_native.restype = C.c_int32
+        L.gh_decode_reduce_native.argtypes = [P, V, V, V, V]
         I32P = C.POINTER(C.c_int32)
         I64P = C.POINTER(C.c_int64)
         L.gh_slot_pool_create.restype = C.c_int32
@@ -127,9 +131,11 @@ def _stream(stream):
 
 
 def make_problem(batch, n_q_heads, n_kv_heads, head_dim, dtype, n_slots, slot_capacity,
-                 max_ctx_len, strides, scale, chunk_rows=0, kernel=GH_KERNEL_AUTO):
+                 max_ctx_len, strides, scale, chunk_rows=0, kernel=GH_KERNEL_AUTO,
+                 q_batch_stride=0, new_batch_stride=0):
     return gh_problem(batch, n_q_heads, n_kv_heads, head_dim, dtype, n_slots, slot_capacity,
-                      max_ctx_len, strides[0], strides[1], strides[2], scale, chunk_rows, kernel)
+                      max_ctx_len, strides[0], strides[1], strides[2], scale, chunk_rows, kernel,
+                      q_batch_stride, new_batch_stride)
 
 
 def gh_status_string(status):
@@ -165,6 +171,11 @@ def gh_decode_attention(p, q, k_cache, v_cache, slot_id, ctx_len, workspace, wor
 def gh_decode_reduce(p, workspace, ctx_len, out, stream=None):
     return lib().gh_decode_reduce(C.byref(p), _ptr(workspace), _ptr(ctx_len), _ptr(out),
                                   _stream(stream))
+
+
+def gh_decode_reduce_native(p, workspace, ctx_len, out16, stream=None):
+    return lib().gh_decode_reduce_native(C.byref(p), _ptr(workspace), _ptr(ctx_len), _ptr(out16),
+                                         _stream(stream))
 
 
 def check(status):

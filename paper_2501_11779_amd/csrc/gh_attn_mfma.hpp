@@ -195,7 +195,7 @@ __device__ __forceinline__ void load_q(u32x4 (&qop)[4], const AttnArgs& a, int b
 #pragma unroll
   for (int kk = 0; kk < 4; ++kk)
     qop[kk] = *reinterpret_cast<const u32x4*>(
-        a.q + ((int64_t)b * a.n_q_heads + head) * kHeadDim + 32 * kk + 8 * c);
+        a.q + (int64_t)b * a.q_batch_stride + head * kHeadDim + 32 * kk + 8 * c);
 }
 __device__ __forceinline__ void keep_real_heads(u32x4 (&dst)[4], const u32x4 (&src)[4], int nh,
                                                 int hn) {

@@ -42,7 +42,7 @@ __global__ __launch_bounds__(256) void attn_valu_kernel(const AttnArgs a) {
   for (int i = 0; i < GT; ++i) {
     if (i < it.nh) {
       const uint4 w = *reinterpret_cast<const uint4*>(
-          a.q + ((int64_t)it.b * a.n_q_heads + it.h0 + i) * kHeadDim + 8 * j);
+          a.q + (int64_t)it.b * a.q_batch_stride + (it.h0 + i) * kHeadDim + 8 * j);
       unpack8<BF16>(w, qf[i]);
 #pragma unroll
       for (int e = 0; e < 8; ++e) qf[i][e] *= a.scale_log2e;

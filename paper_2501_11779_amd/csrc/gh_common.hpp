@@ -21,6 +21,7 @@ struct AttnArgs {
   float* ws_l;              // [B, H, C]
   int32_t* ws_n;            // [B, H]  records in use per head
   int64_t slot_stride, head_stride, row_stride;   // elements
+  int64_t q_batch_stride;                         // elements between sequences in q
   int32_t n_q_heads, n_kv_heads, group;           // H, H_kv, G = H / H_kv
   int32_t n_slots, row_limit;                     // row_limit = min(capacity, max_ctx_len)
   int32_t chunk_rows, n_chunks;

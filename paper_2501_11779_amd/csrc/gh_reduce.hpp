@@ -9,7 +9,7 @@ struct ReduceArgs {
   const float* ws_m;   // [B*H, C]
   const float* ws_l;   // [B*H, C]
   const int32_t* ws_n; // [B*H]  records in use
-  float* out;          // [B*H, 128]
+  void* out;           // [B*H, 128] fp32, or the 16-bit model type
   int64_t n_rows;      // B * H
   int32_t n_chunks;
 };
@@ -24,6 +24,8 @@ __device__ __forceinline__ float wave_max(float x) {
 // are read 64 at a time, one per lane, to find the common maximum and the weights; the o rows
 // are then accumulated in record order with independent loads, so the result does not depend on
 // scheduling.
+// OUT: 0 = fp32, 1 = binary16, 2 = bfloat16 (round to nearest even at the store).
+template <int OUT>
 __global__ __launch_bounds__(256) void decode_reduce_kernel(const ReduceArgs a) {
   const int lane = threadIdx.x & 63;
   const int64_t row = (int64_t)blockIdx.x * 4 + (threadIdx.x >> 6);
@@ -84,7 +86,17 @@ __global__ __launch_bounds__(256) void decode_reduce_kernel(const ReduceArgs a) 
     acc.x /= L;
     acc.y /= L;
   }
-  *reinterpret_cast<float2*>(a.out + row * kHeadDim + 2 * lane) = acc;
+  if constexpr (OUT == 0) {
+    *reinterpret_cast<float2*>(static_cast<float*>(a.out) + row * kHeadDim + 2 * lane) = acc;
+  } else if constexpr (OUT == 1) {
+    typedef _Float16 h2 __attribute__((ext_vector_type(2)));
+    const h2 v = {(_Float16)acc.x, (_Float16)acc.y};
+    reinterpret_cast<h2*>(a.out)[row * (kHeadDim / 2) + lane] = v;
+  } else {
+    typedef __bf16 b2 __attribute__((ext_vector_type(2)));
+    const b2 v = {(__bf16)acc.x, (__bf16)acc.y};
+    reinterpret_cast<b2*>(a.out)[row * (kHeadDim / 2) + lane] = v;
+  }
 }
 
 }  // namespace gh

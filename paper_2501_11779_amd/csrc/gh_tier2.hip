@@ -33,6 +33,12 @@ int32_t check_problem(const gh_problem* p) {
   if (p->row_stride % 8 || p->head_stride % 8 || p->slot_stride % 8) return GH_ERR_UNSUPPORTED;
   if (p->max_ctx_len > p->slot_capacity) return GH_ERR_CAPACITY;
   if (p->chunk_rows < 0 || p->chunk_rows % kChunkQuantum != 0) return GH_ERR_SHAPE;
+  if (p->q_batch_stride < 0 || p->new_batch_stride < 0) return GH_ERR_SHAPE;
+  if (p->q_batch_stride % 8 || p->new_batch_stride % 8) return GH_ERR_UNSUPPORTED;
+  if (p->q_batch_stride != 0 && p->q_batch_stride < (int64_t)p->n_q_heads * p->head_dim)
+    return GH_ERR_SHAPE;
+  if (p->new_batch_stride != 0 && p->new_batch_stride < (int64_t)p->n_kv_heads * p->head_dim)
+    return GH_ERR_SHAPE;
   return GH_OK;
 }
 
@@ -178,6 +184,8 @@ int32_t gh_kv_append(const gh_problem* p, void* k_cache, void* v_cache, const vo
   a.slot_stride = p->slot_stride;
   a.head_stride = p->head_stride;
   a.row_stride = p->row_stride;
+  a.new_batch_stride =
+      p->new_batch_stride ? p->new_batch_stride : (int64_t)p->n_kv_heads * p->head_dim;
   a.batch = p->batch;
   a.n_kv_heads = p->n_kv_heads;
   a.n_slots = p->n_slots;
@@ -216,6 +224,7 @@ int32_t gh_decode_attention(const gh_problem* p, const void* q, const void* k_ca
   a.slot_stride = p->slot_stride;
   a.head_stride = p->head_stride;
   a.row_stride = p->row_stride;
+  a.q_batch_stride = p->q_batch_stride ? p->q_batch_stride : (int64_t)p->n_q_heads * p->head_dim;
   a.n_q_heads = p->n_q_heads;
   a.n_kv_heads = p->n_kv_heads;
   a.group = p->n_q_heads / p->n_kv_heads;
@@ -255,9 +264,13 @@ int32_t gh_decode_attention(const gh_problem* p, const void* q, const void* k_ca
   return hipGetLastError() == hipSuccess ? GH_OK : GH_ERR_HIP;
 }
 
-int32_t gh_decode_reduce(const gh_problem* p, const void* workspace, const int32_t* ctx_len,
-                         float* out, void* hip_stream) {
-  (void)ctx_len;
+}  // extern "C"
+
+namespace {
+
+// out_kind: 0 = fp32, 1 = the problem's 16-bit type
+int32_t launch_reduce(const gh_problem* p, const void* workspace, void* out, int out_kind,
+                      void* hip_stream) {
   const int32_t st = check_problem(p);
   if (st != GH_OK) return st;
   if (p->batch == 0) return GH_OK;
@@ -274,8 +287,30 @@ int32_t gh_decode_reduce(const gh_problem* p, const void* workspace, const int32
   a.n_rows = (int64_t)p->batch * p->n_q_heads;
   a.n_chunks = pl.n_chunks;
   const dim3 grid((unsigned)((a.n_rows + 3) / 4)), block(256);
-  hipLaunchKernelGGL(gh::decode_reduce_kernel, grid, block, 0, static_cast<hipStream_t>(hip_stream), a);
+  hipStream_t s = static_cast<hipStream_t>(hip_stream);
+  if (out_kind == 0)
+    hipLaunchKernelGGL(gh::decode_reduce_kernel<0>, grid, block, 0, s, a);
+  else if (p->dtype == GH_F16)
+    hipLaunchKernelGGL(gh::decode_reduce_kernel<1>, grid, block, 0, s, a);
+  else
+    hipLaunchKernelGGL(gh::decode_reduce_kernel<2>, grid, block, 0, s, a);
   return hipGetLastError() == hipSuccess ? GH_OK : GH_ERR_HIP;
+}
+
+}  // namespace
+
+extern "C" {
+
+int32_t gh_decode_reduce(const gh_problem* p, const void* workspace, const int32_t* ctx_len,
+                         float* out, void* hip_stream) {
+  (void)ctx_len;
+  return launch_reduce(p, workspace, out, 0, hip_stream);
+}
+
+int32_t gh_decode_reduce_native(const gh_problem* p, const void* workspace, const int32_t* ctx_len,
+                                void* out16, void* hip_stream) {
+  (void)ctx_len;
+  return launch_reduce(p, workspace, out16, 1, hip_stream);
 }
 
 }  // extern "C"

@@ -67,6 +67,9 @@ def test_status_strings():
     (dict(max_ctx_len=5000), G.GH_ERR_CAPACITY),
     (dict(chunk_rows=100), G.GH_ERR_SHAPE),
     (dict(chunk_rows=-64), G.GH_ERR_SHAPE),
+    (dict(q_batch_stride=32 * 128 - 8), G.GH_ERR_SHAPE),
+    (dict(new_batch_stride=-8), G.GH_ERR_SHAPE),
+    (dict(q_batch_stride=48 * 128 + 4), G.GH_ERR_UNSUPPORTED),
 ])
 def test_invalid_problems_are_refused_by_every_entry_point(kw, status):
     p = good(**kw)
@@ -77,6 +80,7 @@ def test_invalid_problems_are_refused_by_every_entry_point(kw, status):
     assert G.gh_kv_append(p, fake, fake, fake, fake, fake, fake, None, 0) == status
     assert G.gh_decode_attention(p, fake, fake, fake, fake, fake, fake, 1 << 40, 0) == status
     assert G.gh_decode_reduce(p, fake, None, fake, 0) == status
+    assert G.gh_decode_reduce_native(p, fake, None, fake, 0) == status
 
 
 def test_null_problem_and_null_pointers():
