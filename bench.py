@@ -86,6 +86,9 @@ def main():
                     help="experiment: every sequence has this many cached rows")
     ap.add_argument("--capacity", type=int, default=0,
                     help="experiment: rows per cache slot (default: longest context + 1)")
+    ap.add_argument("--mixed", type=int, default=0, metavar="T",
+                    help="experiment: the last 2*T batch entries become two prefill chunks of T "
+                         "tokens each (entries sharing a slot with consecutive positions)")
     ap.add_argument("--paged", action="store_true",
                     help="keep the caches in a gh_slot_pool (virtual slots, pages mapped on demand)")
     ap.add_argument("--page-rows", type=int, default=1024)
@@ -121,7 +124,19 @@ def main():
             lengths=("const", args.const_len) if args.const_len else w.lengths,
             note=w.note + " [EXPERIMENT: overridden batch/lengths]")
     t0 = time.perf_counter()
-    inp = W.make_inputs(w, "cuda", capacity=args.capacity or None,
+    lengths = slots = None
+    if args.mixed:
+        T = args.mixed
+        assert 2 * T < w.batch
+        lengths = W.draw_lengths(w).copy()
+        slots = W.draw_slots(w, w.batch).copy()
+        for i, base in enumerate((1024, 3000)):            # cached rows of the two prompts
+            first = w.batch - (2 - i) * T
+            lengths[first:first + T] = base + np.arange(T)
+            slots[first:first + T] = slots[first]
+        import dataclasses
+        w = dataclasses.replace(w, note=w.note + f" [EXPERIMENT: two {T}-token prefill chunks]")
+    inp = W.make_inputs(w, "cuda", capacity=args.capacity or None, lengths=lengths, slots=slots,
                         layout="token_major" if args.paged else "head_major")
     torch.cuda.synchronize()
     pool = None
@@ -218,7 +233,8 @@ def main():
                      "frac": achieved / HBM_PEAK_GBS,
                      "traffic": args.traffic_bytes if args.traffic_bytes is not None else (
                          MEASURED_TRAFFIC_BYTES.get(w.name)
-                         if args.kernel == "auto" and not (args.chunk_rows or args.batch or args.const_len or args.capacity or args.paged)
+                         if args.kernel == "auto" and not (args.chunk_rows or args.batch or args.const_len or args.capacity or args.paged
+                                                      or args.mixed)
                          else None),
                      "algorithmic_bytes_per_launch": attn_bytes,
                      "avg_launch_ms": float(attn_ms.mean())},

@@ -32,8 +32,14 @@
  *     nothing.  Conditions only visible on the device (slot id or position
  *     out of range) make the kernel skip that sequence and OR a bit into
  *     *dev_status when that pointer is non-null.  Nothing aborts or prints.
- *   - Caller guarantees (undefined otherwise): slot ids are unique within a
- *     batch, buffers do not alias, ctx_len[b] <= max_ctx_len.
+ *   - Caller guarantees (undefined otherwise): (slot id, position) pairs are
+ *     unique within a batch, buffers do not alias, ctx_len[b] <= max_ctx_len.
+ *   - Mixed prefill/decode batches (Appendix D): a batch entry is a token, and
+ *     several entries may address the same slot with consecutive positions --
+ *     the tokens of a prefill chunk of one prompt.  Each entry attends over
+ *     rows [0, ctx_len) of its slot; since the append of the whole batch runs
+ *     first, entry t of a chunk sees the chunk's earlier tokens and not the
+ *     later ones: causal attention, with no other provision.
  */
 #ifndef GH_TIER2_H
 #define GH_TIER2_H

@@ -98,7 +98,7 @@ def _randn16(shape, dtype, gen, device, chunk_elems=1 << 28):
 
 
 def make_inputs(w: Workload, device="cpu", lengths=None, n_slots=None, capacity=None,
-                layout="head_major", poison=True):
+                layout="head_major", poison=True, slots=None):
     """Build one step's inputs on `device`.
 
     Returns a dict of torch tensors plus the scalar geometry:
@@ -107,14 +107,23 @@ def make_inputs(w: Workload, device="cpu", lengths=None, n_slots=None, capacity=
     Rows at index >= pos[b] of a sequence's slot, and every row of unused
     slots, hold a NaN bit pattern when `poison` is set, so that a read outside
     the problem shows up in the output.
+
+    `slots` overrides the seeded slot assignment; entries may then share a slot
+    (the tokens of a prefill chunk: same slot, consecutive `lengths`), in which
+    case the slot's cached rows end at the smallest of their lengths.
     """
     dt = TORCH_DTYPE[w.dtype]
     L = draw_lengths(w) if lengths is None else np.asarray(lengths, dtype=np.int32)
     assert L.shape == (w.batch,)
     n_slots = w.batch if n_slots is None else n_slots
     capacity = int(L.max()) + 1 if capacity is None else capacity
-    assert n_slots >= w.batch and capacity >= int(L.max()) + 1
-    slot = draw_slots(w, n_slots)
+    assert capacity >= int(L.max()) + 1
+    if slots is None:
+        assert n_slots >= w.batch
+        slot = draw_slots(w, n_slots)
+    else:
+        slot = np.asarray(slots, dtype=np.int32)
+        assert slot.shape == (w.batch,) and slot.min() >= 0 and slot.max() < n_slots
     gen = torch.Generator(device=device)
     gen.manual_seed(w.seed)
     B, H, Hkv, d = w.batch, w.n_q_heads, w.n_kv_heads, w.head_dim
@@ -126,9 +135,10 @@ def make_inputs(w: Workload, device="cpu", lengths=None, n_slots=None, capacity=
     k_cache = _randn16(shape, dt, gen, device)
     v_cache = _randn16(shape, dt, gen, device)
 
-    rows_of_slot = torch.zeros(n_slots, dtype=torch.int64, device=device)
-    rows_of_slot[torch.from_numpy(slot.astype(np.int64)).to(device)] = \
-        torch.from_numpy(L.astype(np.int64)).to(device)
+    rows_np = np.full(n_slots, np.iinfo(np.int64).max, dtype=np.int64)
+    np.minimum.at(rows_np, slot.astype(np.int64), L.astype(np.int64))
+    rows_np[rows_np == np.iinfo(np.int64).max] = 0
+    rows_of_slot = torch.from_numpy(rows_np).to(device)
     row_idx = torch.arange(capacity, device=device)
     live = row_idx[None, :] < rows_of_slot[:, None]                 # [slot, row]
     if layout == "head_major":

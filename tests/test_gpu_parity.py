@@ -222,6 +222,30 @@ def test_bit_reproducible_and_batch_independent(kernel):
     assert np.array_equal(out.cpu().numpy()[0], a[3])
 
 
+# ------------------------------------------------------------------ mixed prefill / decode batch
+@pytest.mark.parametrize("kernel", ["valu", "mfma"])
+@pytest.mark.parametrize("chunk_rows", [64, 0])
+def test_mixed_prefill_and_decode_batch(kernel, chunk_rows):
+    """Batch entries are tokens: prompt A adds a 37-token chunk to 100 cached rows, prompt C starts
+    from an empty slot with 64 tokens, the rest are decode entries of other prompts."""
+    lengths, slots = [], []
+    lengths += [100 + t for t in range(37)]; slots += [2] * 37       # prefill chunk, prompt A
+    lengths += [300, 31, 700]; slots += [0, 5, 6]                    # decode entries
+    lengths += list(range(64)); slots += [3] * 64                    # fresh prompt C
+    lengths += [257]; slots += [1]
+    lengths, slots = np.array(lengths, dtype=np.int32), np.array(slots, dtype=np.int32)
+    order = np.random.default_rng(3).permutation(len(lengths))        # entries in no special order
+    lengths, slots = lengths[order], slots[order]
+    w = small("mixed", len(lengths), 8, 2, "bf16", 68)
+    inp = W.make_inputs(w, DEV, lengths=lengths, n_slots=8, capacity=704, slots=slots)
+    host = Hh.host_copy(inp)
+    got, _, _ = run_gpu(inp, chunk_rows, KERNELS[kernel])
+    want = Hh.oracle_step(inp, host)
+    Hh.assert_parity(got, want, "mixed batch")
+    assert np.array_equal(W.bits(inp["k_cache"]), host["k_cache"])
+    assert np.array_equal(W.bits(inp["v_cache"]), host["v_cache"])
+
+
 # ------------------------------------------------------------------ the merge on its own
 def test_reduce_matches_oracle_merge_of_oracle_partials():
     w = small("red", 3, 4, 2, "bf16", 65)

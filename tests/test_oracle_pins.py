@@ -370,3 +370,36 @@ def test_attention_cost_matches_table5():
         assert W.algorithmic_flops(w, np.full(B, S)) == 2 * macs
         # fused path: the S*H score traffic disappears, q and K/V reads remain
         assert W.attention_bytes(w, np.full(B, S)) == 2 * (B * S * Dkv * 2) + B * D * 2
+
+
+# ---------------------------------------------------------------- prefill chunk = causal attention
+def test_chunk_of_tokens_sharing_a_slot_is_causal_attention():
+    """Appendix D's mixed batches: the tokens of one prompt are batch entries that share a slot
+    with consecutive positions.  After the batch's append, entry t must equal causal attention of
+    token t over the cached rows plus the chunk's tokens 0..t (torch float64, explicit mask)."""
+    L, T, H, Hkv, d = 5, 7, 4, 2, 16
+    rng = np.random.default_rng(18)
+    cap = L + T
+    shape, st = W.cache_shape_and_strides(2, Hkv, cap, d)
+    k = W.round_to_bits(rng.standard_normal(shape), "bf16")
+    v = W.round_to_bits(rng.standard_normal(shape), "bf16")
+    q = W.round_to_bits(rng.standard_normal((T, H, d)), "bf16")
+    kn = W.round_to_bits(rng.standard_normal((T, Hkv, d)), "bf16")
+    vn = W.round_to_bits(rng.standard_normal((T, Hkv, d)), "bf16")
+    slot = np.full(T, 1, dtype=np.int32)
+    pos = (L + np.arange(T)).astype(np.int32)
+    p = O.make_problem(T, H, Hkv, d, O.BF16, 2, cap, 1.0 / math.sqrt(d), st)
+    assert O.kv_append(p, k, v, kn, vn, slot, pos) == 0
+    out = O.decode_attention(p, q, k, v, slot, pos + 1)
+    G_ = H // Hkv
+    for h in range(H):
+        K = torch.from_numpy(_rows(k, st, 1, h // G_, cap, d, "bf16"))
+        V = torch.from_numpy(_rows(v, st, 1, h // G_, cap, d, "bf16"))
+        Q = torch.from_numpy(_val(q, "bf16")[:, h])                     # [T, d]
+        scores = (Q @ K.T) / math.sqrt(d)                               # [T, L+T]
+        allowed = torch.arange(cap)[None, :] <= (L + torch.arange(T))[:, None]
+        scores = scores.masked_fill(~allowed, float("-inf"))
+        want = torch.softmax(scores, dim=1) @ V
+        np.testing.assert_allclose(out[:, h], want.numpy(), rtol=1e-12, atol=1e-13)
+    # the appended rows are the chunk's keys, in token order
+    assert np.array_equal(k.reshape(shape)[1, :, L:L + T], kn.transpose(1, 0, 2))
