@@ -99,7 +99,11 @@ def test_packed_message_in_and_native_result_out(dtype, H, Hkv):
     got_bits = W.bits(out16)
     want_bits = round_f64_to_bits(want, dtype)
     apart = ulps_apart(got_bits, want_bits)
-    assert apart.max() <= 1
+    # ... except next to zero, where one step of the 16-bit type is smaller than the fp32 path's
+    # own absolute error (a few 1e-7) and the distance in steps means nothing
+    far = apart > 1
+    diff = np.abs(W.from_bits(got_bits, dtype).double().numpy() - W.from_bits(want_bits, dtype).double().numpy())
+    assert np.all(diff[far] <= 2e-6)
     assert (apart == 0).mean() > 0.995
     # and it is exactly the fp32 result rounded to nearest even
     assert np.array_equal(got_bits, W.bits(out32.to(W.TORCH_DTYPE[dtype])))
