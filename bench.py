@@ -101,8 +101,9 @@ def main():
                     help="HBM bytes per attention launch from rocprofv3 counters, if measured")
     args = ap.parse_args()
     if args.gpus != 1:
-        sys.exit("bench.py: this build runs on one GPU only (the path shards by sequence with no "
-                 "exchange step; see DESIGN.md); run with --gpus 1")
+        sys.exit("bench.py: this build runs on one GPU only (the path shards by sequence, with no "
+                 "exchange step between shards, but no multi-GPU launcher is part of it); "
+                 "run with --gpus 1")
 
     import numpy as np
     import torch
