@@ -110,6 +110,45 @@ def test_more_than_64_records_per_head(kernel):
     Hh.assert_parity(got, Hh.oracle_step(inp, host), "68 records")
 
 
+def test_largest_batch_of_the_balanced_split():
+    """4096 sequences: the per-sequence arrays fill the kernel's dynamic LDS to its limit."""
+    B = 4096
+    w = W.Workload("lim", B, 4, 2, 128, "bf16", ("uniform", 0, 120), 53)
+    inp = W.make_inputs(w, DEV)
+    host = Hh.host_copy(inp)
+    got, p, _ = run_gpu(inp, 0, G.GH_KERNEL_MFMA)
+    assert G.gh_decode_chunk_rows(p) == 0
+    Hh.assert_parity(got, Hh.oracle_step(inp, host), "B=4096")
+
+
+@pytest.mark.parametrize("kernel", ["valu", "mfma"])
+def test_rows_padded_to_twice_the_head_dim(kernel):
+    """Explicit strides: each cached row sits in a 256-element pitch, slots are padded too."""
+    B, H, Hkv, d, cap, n_slots, pitch = 5, 8, 2, 128, 300, 6, 256
+    L = np.array([0, 100, 299, 64, 33], dtype=np.int32)
+    w = small("pitch", B, H, Hkv, "bf16", 54)
+    inp = W.make_inputs(w, DEV, lengths=L, n_slots=n_slots, capacity=cap)
+    slot_pitch = Hkv * cap * pitch + 1024                      # padding between slots as well
+    def widen(cache):
+        flat = torch.full((n_slots * slot_pitch,), float("nan"), dtype=cache.dtype, device=DEV)
+        view = flat.as_strided((n_slots, Hkv, cap, d), (slot_pitch, cap * pitch, pitch, 1))
+        view.copy_(cache)
+        return flat
+    wide = dict(inp)
+    wide["k_cache"], wide["v_cache"] = widen(inp["k_cache"]), widen(inp["v_cache"])
+    wide["strides"] = (slot_pitch, cap * pitch, pitch)
+    host = Hh.host_copy(wide)
+    got, _, _ = run_gpu(wide, 64 if kernel == "valu" else 0, KERNELS[kernel])
+    po = O.make_problem(B, H, Hkv, d, O.BF16, n_slots, cap, inp["scale"], wide["strides"])
+    assert O.kv_append(po, host["k_cache"], host["v_cache"], host["k_new"], host["v_new"],
+                       host["slot_id"], host["pos"]) == 0
+    want = O.decode_attention(po, host["q"], host["k_cache"], host["v_cache"], host["slot_id"],
+                              host["ctx_len"])
+    Hh.assert_parity(got, want, "pitched rows")
+    assert np.array_equal(W.bits(wide["k_cache"]), host["k_cache"])   # padding untouched, rows exact
+    assert np.array_equal(W.bits(wide["v_cache"]), host["v_cache"])
+
+
 def test_batch_above_the_balanced_split_limit_uses_the_fixed_split():
     """More than 4096 sequences: the library falls back to fixed chunks for the MFMA kernel."""
     B = 4100
