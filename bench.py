@@ -92,6 +92,8 @@ def main():
     ap.add_argument("--paged", action="store_true",
                     help="keep the caches in a gh_slot_pool (virtual slots, pages mapped on demand)")
     ap.add_argument("--page-rows", type=int, default=1024)
+    ap.add_argument("--paged-layout", choices=["token_major", "head_blocked"], default="token_major",
+                    help="order of a page's rows: [row][kv head] or [kv head][row]")
     ap.add_argument("--virtual-capacity", type=int, default=0,
                     help="rows per virtual slot in --paged mode (default: 3x the mean context)")
     ap.add_argument("--pmc-calibration", action="store_true",
@@ -150,13 +152,14 @@ def main():
         need = pages_needed(inp["lengths"], args.page_rows)
         vcap = args.virtual_capacity or max(int(inp["lengths"].max()) + 1,
                                             int(3 * need * args.page_rows / w.batch))
-        pool = G.SlotPool(inp["n_slots"], vcap, w.n_kv_heads, w.head_dim, args.page_rows, need)
+        pool = G.SlotPool(inp["n_slots"], vcap, w.n_kv_heads, w.head_dim, args.page_rows, need,
+                          layout=args.paged_layout)
         inp = into_pool(pool, inp, poison=False)
         st = pool.stats()
         paged_info = {"page_rows": args.page_rows, "page_bytes": st.page_bytes,
                       "virtual_GB": st.virtual_bytes / 1e9, "physical_GB": st.physical_bytes / 1e9,
                       "oversubscription": st.virtual_bytes / st.physical_bytes,
-                      "layout": "token-major, HIP virtual memory"}
+                      "layout": args.paged_layout + ", HIP virtual memory"}
         log(f"paged slots: {paged_info}")
     kernel = {"auto": G.GH_KERNEL_AUTO, "valu": G.GH_KERNEL_VALU, "mfma": G.GH_KERNEL_MFMA}[args.kernel]
     p = G.problem_from_inputs(inp, chunk_rows=args.chunk_rows, kernel=kernel)

@@ -13,11 +13,18 @@
  * slot as the slot's sequence grows.  The kernels of gh_tier2.h run unchanged
  * on the pool's base pointers: they never touch a row at or beyond ctx_len.
  *
- * Layout: token-major, element (slot s, row r, kv head g, column j) at
- *   s*slot_stride + r*row_stride + g*head_stride + j        (elements)
- * with row_stride = n_kv_heads*head_dim, head_stride = head_dim and
- * slot_stride = capacity*row_stride, capacity rounded up to whole pages.  A
- * page holds page_rows consecutive rows of all kv heads of one slot.
+ * A page holds page_rows consecutive rows of all kv heads of one slot; the
+ * capacity is rounded up to whole pages.  Two layouts inside a page:
+ *   GH_POOL_TOKEN_MAJOR  [row][kv head][d]: element (slot s, row r, head g,
+ *     column j) at s*slot_stride + r*row_stride + g*head_stride + j with
+ *     row_stride = n_kv_heads*head_dim, head_stride = head_dim.
+ *   GH_POOL_HEAD_BLOCKED [kv head][row][d]: a head's page_rows rows are
+ *     contiguous inside the page (longer sequential runs for a kernel that
+ *     streams one head); element at s*slot_stride + (r / page_rows)*block_stride
+ *     + g*head_stride + (r % page_rows)*row_stride + j with row_stride =
+ *     head_dim, head_stride = page_rows*head_dim, block_stride = one page.
+ *     page_rows must be a power of two >= 32; gh_problem takes block_rows =
+ *     page_rows and block_stride from gh_slot_pool_blocks().
  *
  * Every function here is a HOST function working on HOST arguments; slot ids
  * and row counts are host arrays (the controller knows each prompt's position).
@@ -37,6 +44,8 @@ extern "C" {
 
 typedef struct gh_slot_pool gh_slot_pool;
 
+enum { GH_POOL_TOKEN_MAJOR = 0, GH_POOL_HEAD_BLOCKED = 1 };
+
 typedef struct {
   int32_t n_slots;        /* slots in the virtual range                               */
   int32_t slot_capacity;  /* rows per slot wanted; rounded up to a multiple of page_rows */
@@ -45,6 +54,7 @@ typedef struct {
   int32_t page_rows;      /* rows per page; page bytes = page_rows*n_kv_heads*head_dim*2
                              must be a multiple of the driver's mapping granularity   */
   int32_t device;         /* HIP device ordinal                                       */
+  int32_t layout;         /* GH_POOL_TOKEN_MAJOR or GH_POOL_HEAD_BLOCKED              */
   int64_t physical_pages; /* budget: pages of K (and as many of V) that exist at all  */
 } gh_slot_pool_config;
 
@@ -74,6 +84,10 @@ void* gh_slot_pool_k(const gh_slot_pool* pool);
 void* gh_slot_pool_v(const gh_slot_pool* pool);
 int32_t gh_slot_pool_strides(const gh_slot_pool* pool, int64_t* slot_stride,
                              int64_t* head_stride, int64_t* row_stride);
+
+/* block_rows and block_stride (elements) for gh_problem: (0, 0) for the
+ * token-major layout, (page_rows, elements of one page) for the head-blocked one. */
+int32_t gh_slot_pool_blocks(const gh_slot_pool* pool, int32_t* block_rows, int64_t* block_stride);
 
 /*
  * Makes sure rows [0, rows[i]) of slot slot_id[i] are backed by pages, for

@@ -24,6 +24,11 @@
  *     s*slot_stride + g*head_stride + r*row_stride + j (in elements); the
  *     `head_dim` elements of one row are contiguous.  K and V are separate
  *     allocations with the same geometry.
+ *   - Blocked layout (block_rows > 0): row r of a head lives at
+ *     (r / block_rows)*block_stride + (r % block_rows)*row_stride instead of
+ *     r*row_stride.  It describes pages that hold block_rows consecutive rows of
+ *     every kv head with each head's rows together ([slot][page][head][row][d]),
+ *     which keeps a head's rows contiguous inside a page.
  *   - Query head h reads kv head h / (n_q_heads / n_kv_heads).
  *   - A cache that holds several layers (a Tier-1 node hosts a range of
  *     layers, Section 4.1.2) is addressed by passing the layer's base pointer:
@@ -96,6 +101,8 @@ typedef struct {
                                set to (H + 2*H_kv)*d the three inputs can be read
                                straight out of one packed per-sequence message
                                q | k | v (Section 5.4.3: what Tier 1 sends).      */
+  int32_t block_rows;       /* 0, or a power of two >= 32: blocked cache layout   */
+  int64_t block_stride;     /* elements between consecutive blocks of one head    */
 } gh_problem;
 
 /* Static text for a status code (host pointer, never null). */

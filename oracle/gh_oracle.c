@@ -61,7 +61,18 @@ typedef struct {
   int64_t head_stride;
   int64_t row_stride;
   double scale;          /* softmax scaling of the scores        */
+  int32_t block_rows;    /* 0, or rows per block of a blocked layout */
+  int64_t block_stride;  /* elements between blocks of one head      */
 } gho_problem;
+
+/* Offset of row r inside a (slot, head) strip.  Plain layouts: r * row_stride.  Blocked layouts
+ * (pages that hold block_rows consecutive rows of every head, each head's rows together):
+ * block r / block_rows starts at that multiple of block_stride, rows inside it are row_stride
+ * apart.  A storage choice only; no arithmetic depends on it. */
+static int64_t row_offset(const gho_problem* p, int64_t r) {
+  if (p->block_rows <= 0) return r * p->row_stride;
+  return (r / p->block_rows) * p->block_stride + (r % p->block_rows) * p->row_stride;
+}
 
 /* IEEE 754 binary16 -> double, exact (subnormals, inf, NaN included). */
 double gho_f16_to_f64(uint16_t h) {
@@ -134,7 +145,7 @@ void gho_kv_append(const gho_problem* p, uint16_t* k_cache, uint16_t* v_cache,
     }
     for (int32_t g = 0; g < p->n_kv_heads; ++g) {
       int64_t dst = (int64_t)slot_id[b] * p->slot_stride +
-                    (int64_t)g * p->head_stride + (int64_t)pos[b] * p->row_stride;
+                    (int64_t)g * p->head_stride + row_offset(p, pos[b]);
       int64_t src = ((int64_t)b * p->n_kv_heads + g) * d;
       memcpy(k_cache + dst, k_new + src, (size_t)d * sizeof(uint16_t));
       memcpy(v_cache + dst, v_new + src, (size_t)d * sizeof(uint16_t));
@@ -153,7 +164,7 @@ static void scores(const gho_problem* p, const uint16_t* q,
   const uint16_t* qv = q + ((int64_t)b * p->n_q_heads + h) * d;
   for (int32_t r = r0; r < r1; ++r) {
     const uint16_t* kr = k_cache + (int64_t)slot * p->slot_stride +
-                         (int64_t)g * p->head_stride + (int64_t)r * p->row_stride;
+                         (int64_t)g * p->head_stride + row_offset(p, r);
     double acc = 0.0;
     for (int64_t j = 0; j < d; ++j)
       acc += widen(p->dtype, qv[j]) * widen(p->dtype, kr[j]);
@@ -192,7 +203,7 @@ void gho_decode_attention(const gho_problem* p, const uint16_t* q,
     for (int32_t r = 0; r < n; ++r) {
       const double w = s[r] / Z;
       const uint16_t* vr = v_cache + (int64_t)slot * p->slot_stride +
-                           (int64_t)g * p->head_stride + (int64_t)r * p->row_stride;
+                           (int64_t)g * p->head_stride + row_offset(p, r);
       for (int64_t j = 0; j < d; ++j) o[j] += w * widen(p->dtype, vr[j]);
     }
     free(s);
@@ -229,7 +240,7 @@ void gho_partial(const gho_problem* p, const uint16_t* q,
     l += w;
     const uint16_t* vr = v_cache + (int64_t)slot * p->slot_stride +
                          (int64_t)g * p->head_stride +
-                         (int64_t)(r0 + r) * p->row_stride;
+                         row_offset(p, r0 + r);
     for (int64_t j = 0; j < d; ++j) o[j] += w * widen(p->dtype, vr[j]);
   }
   free(t);

@@ -29,6 +29,7 @@ class Problem(C.Structure):
         ("slot_capacity", C.c_int32),
         ("slot_stride", C.c_int64), ("head_stride", C.c_int64), ("row_stride", C.c_int64),
         ("scale", C.c_double),
+        ("block_rows", C.c_int32), ("block_stride", C.c_int64),
     ]
 
 
@@ -66,13 +67,14 @@ def _ptr(a):
 
 
 def make_problem(batch, n_q_heads, n_kv_heads, head_dim, dtype, n_slots, slot_capacity,
-                 scale, strides=None):
-    """Cache layout defaults to [slot][kv head][row][d]; strides are in elements."""
+                 scale, strides=None, block=(0, 0)):
+    """Cache layout defaults to [slot][kv head][row][d]; strides are in elements; `block` =
+    (rows per block, elements between a head's blocks) for blocked layouts."""
     if strides is None:
         strides = (n_kv_heads * slot_capacity * head_dim, slot_capacity * head_dim, head_dim)
     assert n_q_heads % n_kv_heads == 0
     return Problem(batch, n_q_heads, n_kv_heads, head_dim, dtype, n_slots, slot_capacity,
-                   strides[0], strides[1], strides[2], float(scale))
+                   strides[0], strides[1], strides[2], float(scale), int(block[0]), int(block[1]))
 
 
 def num_threads():

@@ -25,7 +25,9 @@ EXPORTS = ("gh_status_string", "gh_decode_chunk_rows", "gh_decode_num_chunks",
            "gh_decode_reduce_native")
 POOL_EXPORTS = ("gh_slot_pool_create", "gh_slot_pool_destroy", "gh_slot_pool_k", "gh_slot_pool_v",
                 "gh_slot_pool_strides", "gh_slot_pool_reserve", "gh_slot_pool_release",
-                "gh_slot_pool_mapped_rows", "gh_slot_pool_get_stats")
+                "gh_slot_pool_mapped_rows", "gh_slot_pool_get_stats", "gh_slot_pool_blocks")
+GH_POOL_TOKEN_MAJOR, GH_POOL_HEAD_BLOCKED = 0, 1
+POOL_LAYOUTS = {"token_major": GH_POOL_TOKEN_MAJOR, "head_blocked": GH_POOL_HEAD_BLOCKED}
 
 
 class gh_problem(C.Structure):
@@ -36,6 +38,7 @@ class gh_problem(C.Structure):
         ("slot_stride", C.c_int64), ("head_stride", C.c_int64), ("row_stride", C.c_int64),
         ("scale", C.c_float), ("chunk_rows", C.c_int32), ("kernel", C.c_int32),
         ("q_batch_stride", C.c_int64), ("new_batch_stride", C.c_int64),
+        ("block_rows", C.c_int32), ("block_stride", C.c_int64),
     ]
 
 
@@ -43,7 +46,7 @@ class gh_slot_pool_config(C.Structure):
     _fields_ = [
         ("n_slots", C.c_int32), ("slot_capacity", C.c_int32), ("n_kv_heads", C.c_int32),
         ("head_dim", C.c_int32), ("page_rows", C.c_int32), ("device", C.c_int32),
-        ("physical_pages", C.c_int64),
+        ("layout", C.c_int32), ("physical_pages", C.c_int64),
     ]
 
 
@@ -100,6 +103,8 @@ def lib():
         L.gh_slot_pool_k.argtypes = [V]
         L.gh_slot_pool_v.restype = V
         L.gh_slot_pool_v.argtypes = [V]
+        L.gh_slot_pool_blocks.restype = C.c_int32
+        L.gh_slot_pool_blocks.argtypes = [V, C.POINTER(C.c_int32), I64P]
         L.gh_slot_pool_strides.restype = C.c_int32
         L.gh_slot_pool_strides.argtypes = [V, I64P, I64P, I64P]
         L.gh_slot_pool_reserve.restype = C.c_int32
@@ -132,10 +137,10 @@ def _stream(stream):
 
 def make_problem(batch, n_q_heads, n_kv_heads, head_dim, dtype, n_slots, slot_capacity,
                  max_ctx_len, strides, scale, chunk_rows=0, kernel=GH_KERNEL_AUTO,
-                 q_batch_stride=0, new_batch_stride=0):
+                 q_batch_stride=0, new_batch_stride=0, block=(0, 0)):
     return gh_problem(batch, n_q_heads, n_kv_heads, head_dim, dtype, n_slots, slot_capacity,
                       max_ctx_len, strides[0], strides[1], strides[2], scale, chunk_rows, kernel,
-                      q_batch_stride, new_batch_stride)
+                      q_batch_stride, new_batch_stride, int(block[0]), int(block[1]))
 
 
 def gh_status_string(status):
@@ -191,7 +196,7 @@ def problem_from_inputs(inp, chunk_rows=0, kernel=GH_KERNEL_AUTO, max_ctx_len=No
         max_ctx_len = int(inp["lengths"].max()) + 1
     return make_problem(w.batch, w.n_q_heads, w.n_kv_heads, w.head_dim, dtype, inp["n_slots"],
                         inp["capacity"], max_ctx_len, inp["strides"], inp["scale"], chunk_rows,
-                        kernel)
+                        kernel, block=inp.get("block", (0, 0)))
 
 
 def alloc_workspace(p, device="cuda"):
@@ -229,10 +234,11 @@ class SlotPool:
     """Marshalling front end of gh_slot_pool_* (include/gh_slot_pool.h)."""
 
     def __init__(self, n_slots, slot_capacity, n_kv_heads, head_dim, page_rows, physical_pages,
-                 device=0):
+                 device=0, layout="token_major"):
         self._h = C.c_void_p()
         cfg = gh_slot_pool_config(n_slots, slot_capacity, n_kv_heads, head_dim, page_rows, device,
-                                  physical_pages)
+                                  POOL_LAYOUTS[layout], physical_pages)
+        self.layout = layout
         check(lib().gh_slot_pool_create(C.byref(cfg), C.byref(self._h)))
         self.n_slots, self.n_kv_heads, self.head_dim = n_slots, n_kv_heads, head_dim
         self.page_rows = page_rows
@@ -263,6 +269,13 @@ class SlotPool:
         check(lib().gh_slot_pool_strides(self._h, C.byref(a), C.byref(b), C.byref(c)))
         return (a.value, b.value, c.value)
 
+    @property
+    def block(self):
+        """(block_rows, block_stride) for gh_problem."""
+        r, s = C.c_int32(), C.c_int64()
+        check(lib().gh_slot_pool_blocks(self._h, C.byref(r), C.byref(s)))
+        return (r.value, s.value)
+
     def reserve(self, slot_ids, rows):
         s, n = _i32_array(slot_ids)
         r, _ = _i32_array(rows)
@@ -281,10 +294,17 @@ class SlotPool:
         return st
 
     def rows_view(self, which, slot, rows, dtype):
-        """Torch view [rows, H_kv, d] of the first `rows` rows of a slot; they must be reserved."""
+        """Torch view [rows, H_kv, d] of the first `rows` rows of a slot; they must be reserved.
+        In the head-blocked layout `rows` counts whole pages and the view is a permutation of the
+        pages' [page][H_kv][page_rows][d] storage (not contiguous, but writable in place)."""
         assert 0 <= rows <= self.mapped_rows(slot)
         base = self.k_ptr if which == "k" else self.v_ptr
         ptr = base + slot * self.strides[0] * 2
+        if self.layout == "head_blocked":
+            assert rows % self.page_rows == 0
+            shape = (rows // self.page_rows, self.n_kv_heads, self.page_rows, self.head_dim)
+            view = torch.as_tensor(_DeviceArrayView(ptr, shape), device="cuda").view(dtype)
+            return view.permute(0, 2, 1, 3)          # [page][row in page][H_kv][d]
         view = torch.as_tensor(_DeviceArrayView(ptr, (rows, self.n_kv_heads, self.head_dim)),
                                device="cuda")
         return view.view(dtype)

@@ -14,6 +14,8 @@ struct AppendArgs {
   int32_t* dev_status;       // nullable
   int64_t slot_stride, head_stride, row_stride;
   int64_t new_batch_stride;  // elements between sequences in k_new / v_new
+  int64_t block_stride;      // blocked layout, see row_offset()
+  int32_t block_shift, block_mask;
   int32_t batch, n_kv_heads, n_slots, capacity;
 };
 
@@ -34,7 +36,7 @@ __global__ __launch_bounds__(256) void kv_append_kernel(const AppendArgs a) {
     return;
   }
   const int64_t dst = (int64_t)slot * a.slot_stride + (int64_t)g * a.head_stride +
-                      (int64_t)p * a.row_stride + 8 * j;
+                      row_offset(p, a.row_stride, a.block_stride, a.block_shift, a.block_mask) + 8 * j;
   const int64_t src = (int64_t)b * a.new_batch_stride + g * kHeadDim + 8 * j;
   const uint16_t* from = which ? a.v_new : a.k_new;
   uint16_t* to = which ? a.v_cache : a.k_cache;

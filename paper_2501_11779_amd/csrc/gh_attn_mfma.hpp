@@ -94,7 +94,7 @@ __device__ __forceinline__ u32x4 lower_from_rotated(const u32x4& keep, const u32
 }
 
 __device__ __forceinline__ void load_tile(TileRegs& t, const uint16_t* kbase, const uint16_t* vbase,
-                                          int64_t row_stride, int tile_row0, int last, int hn, int c) {
+                                          const AttnArgs& a, int tile_row0, int last, int hn, int c) {
   // K: one load covers 8 rows x 128 bytes (whole cache lines): lanes hn < 8 take the first
   // 64 bytes of the half-row, lanes hn >= 8 the second 64 bytes of the same row.
 #pragma unroll
@@ -104,7 +104,8 @@ __device__ __forceinline__ void load_tile(TileRegs& t, const uint16_t* kbase, co
       const int mrow = (hn & 7) + 8 * ab;                          // row index within the sub-tile
       int row = tile_row0 + 16 * T + 4 * (mrow & 3) + (mrow >> 2);  // rho(T, mrow)
       row = row < last ? row : last;
-      const uint16_t* kp = kbase + (int64_t)row * row_stride + 32 * (hn >> 3) + 8 * c;
+      const uint16_t* kp = kbase + row_offset(row, a.row_stride, a.block_stride, a.block_shift, a.block_mask) +
+                           32 * (hn >> 3) + 8 * c;
 #pragma unroll
       for (int half = 0; half < 2; ++half) t.k[T][half][ab] = stream_load(kp + 64 * half);
     }
@@ -113,7 +114,8 @@ __device__ __forceinline__ void load_tile(TileRegs& t, const uint16_t* kbase, co
   for (int e = 0; e < 8; ++e) {
     int row = tile_row0 + 16 * (e >> 2) + 4 * (e & 3) + c;
     row = row < last ? row : last;
-    t.v[e] = stream_load(vbase + (int64_t)row * row_stride + 8 * hn);
+    t.v[e] = stream_load(vbase + row_offset(row, a.row_stride, a.block_stride, a.block_shift, a.block_mask) +
+                         8 * hn);
   }
 }
 
@@ -228,11 +230,11 @@ __device__ __forceinline__ void run_strip(const AttnArgs& a, int b, int h0, int 
   // clamped to the last row, whose lines are already in cache) so that the number of outstanding
   // loads is known at every wait and a tile's arithmetic overlaps the next tile's loads.
   TileRegs ta, tb;
-  load_tile(ta, kbase, vbase, a.row_stride, r0, last, hn, c);
+  load_tile(ta, kbase, vbase, a, r0, last, hn, c);
   for (int row0 = r0; row0 < r1; row0 += 64) {
-    load_tile(tb, kbase, vbase, a.row_stride, row0 + 32, last, hn, c);
+    load_tile(tb, kbase, vbase, a, row0 + 32, last, hn, c);
     process_tile<BF16>(ta, qop, acc, m, l, a.scale_log2e, row0, r1, c);
-    load_tile(ta, kbase, vbase, a.row_stride, row0 + 64, last, hn, c);
+    load_tile(ta, kbase, vbase, a, row0 + 64, last, hn, c);
     if (row0 + 32 < r1) process_tile<BF16>(tb, qop, acc, m, l, a.scale_log2e, row0 + 32, r1, c);
   }
 
@@ -414,7 +416,7 @@ __global__ __launch_bounds__(256, 2) void attn_mfma_balanced_kernel(const AttnAr
     // and no cache address is touched that the caller did not declare attended (a paged cache
     // may have nothing mapped there).
     load_tile(regs, cu.n > 0 ? a.k_cache + strip : a.q, cu.n > 0 ? a.v_cache + strip : a.q,
-              a.row_stride, (int)cu.lt * 32, cu.n > 0 ? cu.n - 1 : 0, hn, c);
+              a, (int)cu.lt * 32, cu.n > 0 ? cu.n - 1 : 0, hn, c);
   };
 
   // cursor of the tile being computed; start: largest b with cum[b] <= t0

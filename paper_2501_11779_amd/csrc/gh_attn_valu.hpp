@@ -71,7 +71,8 @@ __global__ __launch_bounds__(256) void attn_valu_kernel(const AttnArgs a) {
 #pragma unroll
     for (int u = 0; u < UNROLL; ++u) {
       const int row = r + 16 * u;
-      const int64_t off = (int64_t)(row < last ? row : last) * a.row_stride;
+      const int64_t off = row_offset(row < last ? row : last, a.row_stride, a.block_stride,
+                                     a.block_shift, a.block_mask);
       kw[u] = __builtin_bit_cast(uint4, stream_load(kbase + off));
       vw[u] = __builtin_bit_cast(uint4, stream_load(vbase + off));
     }

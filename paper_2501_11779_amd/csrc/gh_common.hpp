@@ -22,6 +22,8 @@ struct AttnArgs {
   int32_t* ws_n;            // [B, H]  records in use per head
   int64_t slot_stride, head_stride, row_stride;   // elements
   int64_t q_batch_stride;                         // elements between sequences in q
+  int64_t block_stride;                           // blocked layout, see row_offset()
+  int32_t block_shift, block_mask;                // log2(block_rows), block_rows - 1
   int32_t n_q_heads, n_kv_heads, group;           // H, H_kv, G = H / H_kv
   int32_t n_slots, row_limit;                     // row_limit = min(capacity, max_ctx_len)
   int32_t chunk_rows, n_chunks;
@@ -31,6 +33,14 @@ struct AttnArgs {
   int32_t n_workers, min_share;                   // balanced split: waves, least tiles per wave
   float scale_log2e;                              // scale * log2(e)
 };
+
+// Offset of row r inside a (slot, head) strip.  Blocked layouts place block r >> shift at that
+// multiple of block_stride and the rows of a block row_stride apart; a plain layout is the case
+// shift = 31, mask = 0x7fffffff (one block holding every row).
+__device__ __forceinline__ int64_t row_offset(int r, int64_t row_stride, int64_t block_stride,
+                                              int shift, int mask) {
+  return (int64_t)(r >> shift) * block_stride + (int64_t)(r & mask) * row_stride;
+}
 
 // One unit of work: (sequence, kv head, head pass, chunk).  The chunk index
 // varies fastest so that the chunks of one strip are in flight together.

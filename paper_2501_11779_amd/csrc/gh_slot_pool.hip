@@ -65,6 +65,10 @@ int32_t gh_slot_pool_create(const gh_slot_pool_config* cfg, gh_slot_pool** out) 
       cfg->physical_pages <= 0 || cfg->device < 0)
     return kShape;
   if (cfg->head_dim != 128) return kUnsupported;
+  if (cfg->layout != GH_POOL_TOKEN_MAJOR && cfg->layout != GH_POOL_HEAD_BLOCKED) return kUnsupported;
+  if (cfg->layout == GH_POOL_HEAD_BLOCKED &&
+      (cfg->page_rows < 32 || (cfg->page_rows & (cfg->page_rows - 1)) != 0))
+    return kUnsupported;
   int n_dev = 0;
   if (hipGetDeviceCount(&n_dev) != hipSuccess || cfg->device >= n_dev) return kHip;
   if (hipSetDevice(cfg->device) != hipSuccess) return kHip;
@@ -153,9 +157,22 @@ void* gh_slot_pool_v(const gh_slot_pool* p) { return p ? p->v_va : nullptr; }
 int32_t gh_slot_pool_strides(const gh_slot_pool* p, int64_t* slot_stride, int64_t* head_stride,
                              int64_t* row_stride) {
   if (!p || !slot_stride || !head_stride || !row_stride) return kNull;
-  *row_stride = (int64_t)p->cfg.n_kv_heads * p->cfg.head_dim;
-  *head_stride = p->cfg.head_dim;
-  *slot_stride = (int64_t)p->capacity * *row_stride;
+  if (p->cfg.layout == GH_POOL_HEAD_BLOCKED) {
+    *row_stride = p->cfg.head_dim;
+    *head_stride = (int64_t)p->cfg.page_rows * p->cfg.head_dim;
+  } else {
+    *row_stride = (int64_t)p->cfg.n_kv_heads * p->cfg.head_dim;
+    *head_stride = p->cfg.head_dim;
+  }
+  *slot_stride = (int64_t)p->capacity * p->cfg.n_kv_heads * p->cfg.head_dim;
+  return kOk;
+}
+
+int32_t gh_slot_pool_blocks(const gh_slot_pool* p, int32_t* block_rows, int64_t* block_stride) {
+  if (!p || !block_rows || !block_stride) return kNull;
+  const bool blocked = p->cfg.layout == GH_POOL_HEAD_BLOCKED;
+  *block_rows = blocked ? p->cfg.page_rows : 0;
+  *block_stride = blocked ? (int64_t)p->cfg.page_rows * p->cfg.n_kv_heads * p->cfg.head_dim : 0;
   return kOk;
 }
 

@@ -16,6 +16,21 @@ constexpr int kMinAutoChunk = 256;
 
 int round_up(int x, int q) { return (x + q - 1) / q * q; }
 
+// Blocked-layout parameters for the kernels; a plain layout is one block holding every row.
+void block_params(const gh_problem* p, int64_t* stride, int32_t* shift, int32_t* mask) {
+  if (p->block_rows > 0) {
+    int s = 0;
+    while ((1 << s) < p->block_rows) ++s;
+    *shift = s;
+    *mask = p->block_rows - 1;
+    *stride = p->block_stride;
+  } else {
+    *shift = 31;
+    *mask = 0x7fffffff;
+    *stride = 0;
+  }
+}
+
 bool aligned16(const void* p) { return (reinterpret_cast<uintptr_t>(p) & 15u) == 0; }
 
 // Everything about gh_problem that can be judged on the host.
@@ -33,6 +48,10 @@ int32_t check_problem(const gh_problem* p) {
   if (p->row_stride % 8 || p->head_stride % 8 || p->slot_stride % 8) return GH_ERR_UNSUPPORTED;
   if (p->max_ctx_len > p->slot_capacity) return GH_ERR_CAPACITY;
   if (p->chunk_rows < 0 || p->chunk_rows % kChunkQuantum != 0) return GH_ERR_SHAPE;
+  if (p->block_rows < 0 || (p->block_rows > 0 && p->block_stride <= 0)) return GH_ERR_SHAPE;
+  if (p->block_rows > 0 && (p->block_rows < 32 || (p->block_rows & (p->block_rows - 1)) != 0))
+    return GH_ERR_UNSUPPORTED;
+  if (p->block_rows > 0 && p->block_stride % 8) return GH_ERR_UNSUPPORTED;
   if (p->q_batch_stride < 0 || p->new_batch_stride < 0) return GH_ERR_SHAPE;
   if (p->q_batch_stride % 8 || p->new_batch_stride % 8) return GH_ERR_UNSUPPORTED;
   if (p->q_batch_stride != 0 && p->q_batch_stride < (int64_t)p->n_q_heads * p->head_dim)
@@ -186,6 +205,7 @@ int32_t gh_kv_append(const gh_problem* p, void* k_cache, void* v_cache, const vo
   a.row_stride = p->row_stride;
   a.new_batch_stride =
       p->new_batch_stride ? p->new_batch_stride : (int64_t)p->n_kv_heads * p->head_dim;
+  block_params(p, &a.block_stride, &a.block_shift, &a.block_mask);
   a.batch = p->batch;
   a.n_kv_heads = p->n_kv_heads;
   a.n_slots = p->n_slots;
@@ -225,6 +245,7 @@ int32_t gh_decode_attention(const gh_problem* p, const void* q, const void* k_ca
   a.head_stride = p->head_stride;
   a.row_stride = p->row_stride;
   a.q_batch_stride = p->q_batch_stride ? p->q_batch_stride : (int64_t)p->n_q_heads * p->head_dim;
+  block_params(p, &a.block_stride, &a.block_shift, &a.block_mask);
   a.n_q_heads = p->n_q_heads;
   a.n_kv_heads = p->n_kv_heads;
   a.group = p->n_q_heads / p->n_kv_heads;

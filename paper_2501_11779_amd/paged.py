@@ -26,9 +26,16 @@ def into_pool(pool, inp, extra_rows=1, poison=True):
             view = pool.rows_view(which, s, mapped, dt)
             if poison:
                 view.fill_(float("nan"))
-            view[:n] = cache[s, :n]
+            if pool.layout == "head_blocked":        # [page][row in page][H_kv][d]
+                pr, full = pool.page_rows, n // pool.page_rows
+                view[:full] = cache[s, :full * pr].reshape(full, pr, *cache.shape[2:])
+                if n > full * pr:
+                    view[full, :n - full * pr] = cache[s, full * pr:n]
+            else:
+                view[:n] = cache[s, :n]
     torch.cuda.synchronize()
     paged = dict(inp)
     paged["k_cache"], paged["v_cache"] = pool.k_ptr, pool.v_ptr
     paged["strides"], paged["capacity"], paged["n_slots"] = pool.strides, pool.capacity, pool.n_slots
+    paged["block"] = pool.block
     return paged

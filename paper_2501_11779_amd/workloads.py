@@ -72,7 +72,8 @@ def draw_slots(w: Workload, n_slots: int) -> np.ndarray:
     return rng.permutation(n_slots)[: w.batch].astype(np.int32)
 
 
-def cache_shape_and_strides(n_slots, n_kv_heads, capacity, head_dim, layout="head_major"):
+def cache_shape_and_strides(n_slots, n_kv_heads, capacity, head_dim, layout="head_major",
+                            block_rows=0):
     """Tensor shape of one cache and its (slot, head, row) strides in elements."""
     if layout == "head_major":      # [slot][kv head][row][d]
         shape = (n_slots, n_kv_heads, capacity, head_dim)
@@ -80,6 +81,10 @@ def cache_shape_and_strides(n_slots, n_kv_heads, capacity, head_dim, layout="hea
     elif layout == "token_major":   # [slot][row][kv head][d]
         shape = (n_slots, capacity, n_kv_heads, head_dim)
         strides = (capacity * n_kv_heads * head_dim, head_dim, n_kv_heads * head_dim)
+    elif layout == "head_blocked":  # [slot][block][kv head][row in block][d]
+        assert block_rows > 0 and capacity % block_rows == 0
+        shape = (n_slots, capacity // block_rows, n_kv_heads, block_rows, head_dim)
+        strides = (capacity * n_kv_heads * head_dim, block_rows * head_dim, head_dim)
     else:
         raise ValueError(layout)
     return shape, strides
@@ -98,7 +103,7 @@ def _randn16(shape, dtype, gen, device, chunk_elems=1 << 28):
 
 
 def make_inputs(w: Workload, device="cpu", lengths=None, n_slots=None, capacity=None,
-                layout="head_major", poison=True, slots=None):
+                layout="head_major", poison=True, slots=None, block_rows=0):
     """Build one step's inputs on `device`.
 
     Returns a dict of torch tensors plus the scalar geometry:
@@ -107,6 +112,10 @@ def make_inputs(w: Workload, device="cpu", lengths=None, n_slots=None, capacity=
     Rows at index >= pos[b] of a sequence's slot, and every row of unused
     slots, hold a NaN bit pattern when `poison` is set, so that a read outside
     the problem shows up in the output.
+
+    layout "head_blocked" stores blocks of `block_rows` rows, [slot][block][kv head][row][d]; the
+    capacity is rounded up to whole blocks and the dict carries "block" = (block_rows, elements
+    between a head's consecutive blocks).
 
     `slots` overrides the seeded slot assignment; entries may then share a slot
     (the tokens of a prefill chunk: same slot, consecutive `lengths`), in which
@@ -118,6 +127,8 @@ def make_inputs(w: Workload, device="cpu", lengths=None, n_slots=None, capacity=
     n_slots = w.batch if n_slots is None else n_slots
     capacity = int(L.max()) + 1 if capacity is None else capacity
     assert capacity >= int(L.max()) + 1
+    if layout == "head_blocked":
+        capacity = -(-capacity // block_rows) * block_rows
     if slots is None:
         assert n_slots >= w.batch
         slot = draw_slots(w, n_slots)
@@ -127,7 +138,7 @@ def make_inputs(w: Workload, device="cpu", lengths=None, n_slots=None, capacity=
     gen = torch.Generator(device=device)
     gen.manual_seed(w.seed)
     B, H, Hkv, d = w.batch, w.n_q_heads, w.n_kv_heads, w.head_dim
-    shape, strides = cache_shape_and_strides(n_slots, Hkv, capacity, d, layout)
+    shape, strides = cache_shape_and_strides(n_slots, Hkv, capacity, d, layout, block_rows)
 
     q = _randn16((B, H, d), dt, gen, device)
     k_new = _randn16((B, Hkv, d), dt, gen, device)
@@ -143,13 +154,15 @@ def make_inputs(w: Workload, device="cpu", lengths=None, n_slots=None, capacity=
     live = row_idx[None, :] < rows_of_slot[:, None]                 # [slot, row]
     if layout == "head_major":
         live4 = live[:, None, :, None]
+    elif layout == "head_blocked":
+        live4 = live.reshape(n_slots, capacity // block_rows, 1, block_rows, 1)
     else:
         live4 = live[:, :, None, None]
 
     if w.outlier_key_frac > 0.0:
         # i.i.d. Bernoulli per (slot, kv head, row); the whole key row is scaled by 8,
         # which is exact in both 16-bit formats for N(0,1) magnitudes.
-        mshape = shape[:3]
+        mshape = shape[:-1]
         hit = torch.rand(mshape, generator=gen, device=device) < w.outlier_key_frac
         k_cache = torch.where(hit[..., None], k_cache * 8, k_cache)
 
@@ -166,6 +179,7 @@ def make_inputs(w: Workload, device="cpu", lengths=None, n_slots=None, capacity=
         "ctx_len": (pos + 1).to(torch.int32),
         "lengths": L, "slots": slot, "n_slots": n_slots, "capacity": capacity,
         "strides": strides, "layout": layout, "scale": float(np.float32(1.0 / np.sqrt(d))),
+        "block": (block_rows, block_rows * Hkv * d) if layout == "head_blocked" else (0, 0),
     }
 
 

@@ -43,7 +43,9 @@ def oracle_problem(inp, batch=None, n_slots=None):
                           n_slots if n_slots is not None else inp["n_slots"], inp["capacity"],
                           inp["scale"], inp["strides"] if n_slots is None else
                           W.cache_shape_and_strides(n_slots, w.n_kv_heads, inp["capacity"],
-                                                    w.head_dim, inp["layout"])[1])
+                                                    w.head_dim, inp["layout"],
+                                                    inp.get("block", (0, 0))[0])[1],
+                          block=inp.get("block", (0, 0)))
 
 
 def oracle_step(inp, host, append=True):

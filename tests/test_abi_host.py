@@ -40,10 +40,15 @@ def test_slot_pool_symbols_are_exported_and_arguments_checked_without_a_gpu():
         assert getattr(L, n) is not None
     handle = C.c_void_p()
     assert L.gh_slot_pool_create(None, C.byref(handle)) == G.GH_ERR_NULL
-    cfg = G.gh_slot_pool_config(0, 100, 2, 128, 256, 0, 4)
+    cfg = G.gh_slot_pool_config(0, 100, 2, 128, 256, 0, 0, 4)
     assert L.gh_slot_pool_create(C.byref(cfg), C.byref(handle)) == G.GH_ERR_SHAPE
-    cfg = G.gh_slot_pool_config(4, 100, 2, 64, 256, 0, 4)
+    cfg = G.gh_slot_pool_config(4, 100, 2, 64, 256, 0, 0, 4)
     assert L.gh_slot_pool_create(C.byref(cfg), C.byref(handle)) == G.GH_ERR_UNSUPPORTED
+    cfg = G.gh_slot_pool_config(4, 100, 2, 128, 256, 0, 7, 4)                 # unknown layout
+    assert L.gh_slot_pool_create(C.byref(cfg), C.byref(handle)) == G.GH_ERR_UNSUPPORTED
+    cfg = G.gh_slot_pool_config(4, 100, 2, 128, 96, 0, G.GH_POOL_HEAD_BLOCKED, 4)
+    assert L.gh_slot_pool_create(C.byref(cfg), C.byref(handle)) == G.GH_ERR_UNSUPPORTED
+    assert L.gh_slot_pool_blocks(None, None, None) == G.GH_ERR_NULL
     assert L.gh_slot_pool_destroy(None) == G.GH_ERR_NULL
     assert L.gh_slot_pool_k(None) is None and L.gh_slot_pool_mapped_rows(None, 0) == 0
     assert L.gh_slot_pool_reserve(None, None, None, 0) == G.GH_ERR_NULL
@@ -69,6 +74,11 @@ def test_status_strings():
     (dict(chunk_rows=-64), G.GH_ERR_SHAPE),
     (dict(q_batch_stride=32 * 128 - 8), G.GH_ERR_SHAPE),
     (dict(new_batch_stride=-8), G.GH_ERR_SHAPE),
+    (dict(block=(-32, 4096)), G.GH_ERR_SHAPE),
+    (dict(block=(64, 0)), G.GH_ERR_SHAPE),
+    (dict(block=(48, 8 * 48 * 128)), G.GH_ERR_UNSUPPORTED),
+    (dict(block=(16, 8 * 16 * 128)), G.GH_ERR_UNSUPPORTED),
+    (dict(block=(64, 8 * 64 * 128 + 4)), G.GH_ERR_UNSUPPORTED),
     (dict(q_batch_stride=48 * 128 + 4), G.GH_ERR_UNSUPPORTED),
 ])
 def test_invalid_problems_are_refused_by_every_entry_point(kw, status):

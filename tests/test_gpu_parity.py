@@ -170,6 +170,23 @@ def test_token_major_layout(kernel):
     Hh.assert_parity(got, Hh.oracle_step(inp, host), "token-major")
 
 
+@pytest.mark.parametrize("chunk_rows", [0, 128])
+@pytest.mark.parametrize("block_rows", [32, 256])
+@pytest.mark.parametrize("kernel", ["valu", "mfma"])
+def test_head_blocked_layout(kernel, block_rows, chunk_rows):
+    """[slot][block][kv head][row][d]: lengths on, just before and just after block borders; the
+    step's append must land in the right block as well (checked bit for bit on the whole cache)."""
+    w = small("blk", 8, 8, 2, "bf16", 53)
+    L = np.array([0, 31, 32, 255, 256, 257, 600, 1023], dtype=np.int32)
+    inp = W.make_inputs(w, DEV, lengths=L, n_slots=9, layout="head_blocked", block_rows=block_rows)
+    assert inp["capacity"] == 1024
+    host = Hh.host_copy(inp)
+    got, _, _ = run_gpu(inp, chunk_rows, KERNELS[kernel])
+    Hh.assert_parity(got, Hh.oracle_step(inp, host), "head-blocked")
+    assert np.array_equal(W.bits(inp["k_cache"]), host["k_cache"])
+    assert np.array_equal(W.bits(inp["v_cache"]), host["v_cache"])
+
+
 @pytest.mark.parametrize("kernel", ["valu", "mfma"])
 def test_config1_whole_output(kernel):
     inp = W.make_inputs(W.WORKLOADS["c1"], DEV)

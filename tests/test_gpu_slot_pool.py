@@ -60,14 +60,32 @@ def test_pool_refuses_bad_configurations():
     assert e.value.status == G.GH_ERR_UNSUPPORTED
 
 
+def _first_rows(pool, which, slot, n, dt):
+    """Bits of rows [0, n) of a slot as [n, H_kv, d], whatever the pool's layout."""
+    view = pool.rows_view(which, slot, pool.mapped_rows(slot), dt)
+    return W.bits(view.reshape(-1, pool.n_kv_heads, pool.head_dim)[:n])
+
+
+def test_head_blocked_pool_reports_its_geometry():
+    pool = G.SlotPool(4, 1000, 2, 128, 256, physical_pages=4, layout="head_blocked")
+    assert pool.capacity == 1024
+    assert pool.strides == (1024 * 256, 256 * 128, 128)
+    assert pool.block == (256, 256 * 2 * 128)
+    pool.close()
+    pool = G.SlotPool(4, 1000, 2, 128, 256, physical_pages=4)
+    assert pool.block == (0, 0)
+    pool.close()
+
+
+@pytest.mark.parametrize("layout", ["token_major", "head_blocked"])
 @pytest.mark.parametrize("dtype", ["f16", "bf16"])
-def test_decode_step_on_paged_slots_matches_oracle(dtype):
+def test_decode_step_on_paged_slots_matches_oracle(dtype, layout):
     lengths = np.array([0, 255, 256, 257, 700, 31, 1023], dtype=np.int32)
     w = W.Workload("paged", len(lengths), 8, 2, 128, dtype, ("const", 0), 71)
     inp = W.make_inputs(w, DEV, lengths=lengths, n_slots=12, capacity=1024, layout="token_major")
     host = Hh.host_copy(inp)
     need = pages_needed(lengths, 256)
-    pool = G.SlotPool(12, 1024, 2, 128, 256, physical_pages=need)          # not one page to spare
+    pool = G.SlotPool(12, 1024, 2, 128, 256, physical_pages=need, layout=layout)   # none to spare
     assert pool.stats().virtual_bytes / pool.stats().physical_bytes > 3.0
     paged = into_pool(pool, inp)
     assert pool.stats().pages_mapped == need
@@ -84,18 +102,19 @@ def test_decode_step_on_paged_slots_matches_oracle(dtype):
     dt = W.TORCH_DTYPE[dtype]
     for b in range(w.batch):
         s, n = int(inp["slots"][b]), int(lengths[b]) + 1
-        assert np.array_equal(W.bits(pool.rows_view("k", s, n, dt)), host["k_cache"][s, :n])
-        assert np.array_equal(W.bits(pool.rows_view("v", s, n, dt)), host["v_cache"][s, :n])
+        assert np.array_equal(_first_rows(pool, "k", s, n, dt), host["k_cache"][s, :n])
+        assert np.array_equal(_first_rows(pool, "v", s, n, dt), host["v_cache"][s, :n])
     pool.close()
 
 
-def test_slots_grow_page_by_page_and_are_reused():
+@pytest.mark.parametrize("layout", ["token_major", "head_blocked"])
+def test_slots_grow_page_by_page_and_are_reused(layout):
     """Decode steps push a sequence across a page border; a finished prompt's slot is taken over."""
     w = W.Workload("grow", 2, 4, 2, 128, "bf16", ("const", 0), 72)
     lengths = np.array([254, 40], dtype=np.int32)
     inp = W.make_inputs(w, DEV, lengths=lengths, n_slots=3, capacity=512, layout="token_major")
     host = Hh.host_copy(inp)
-    pool = G.SlotPool(3, 512, 2, 128, 256, physical_pages=3)
+    pool = G.SlotPool(3, 512, 2, 128, 256, physical_pages=3, layout=layout)
     paged = into_pool(pool, inp)
     assert pool.stats().pages_mapped == 2
     out = torch.empty((2, 4, 128), dtype=torch.float32, device=DEV)

@@ -203,6 +203,28 @@ def test_token_major_layout_gives_same_result():
     assert np.array_equal(a, b)
 
 
+def test_blocked_layout_gives_same_result_and_append_lands_on_the_same_row():
+    """[slot][block][kv head][row in block][d] is a storage choice: numpy moves the rows, the
+    oracle must give the identical doubles, and an append must land on the moved row."""
+    B, H, Hkv, d, br, cap = 2, 4, 2, 8, 4, 16
+    n = [9, 14]
+    p, q, k, v, slot, nn, st = _case(B, H, Hkv, d, n, cap=cap, seed=13)
+    a = O.decode_attention(p, q, k, v, slot, nn)
+    shape2, st2 = W.cache_shape_and_strides(B, Hkv, cap, d, "head_blocked", br)
+    to_blocked = lambda x: x.reshape(B, Hkv, cap // br, br, d).transpose(0, 2, 1, 3, 4).copy()
+    k2, v2 = to_blocked(k), to_blocked(v)
+    assert k2.shape == shape2
+    p2 = O.make_problem(B, H, Hkv, d, O.BF16, B, cap, 1.0 / math.sqrt(d), st2,
+                        block=(br, br * Hkv * d))
+    assert np.array_equal(a, O.decode_attention(p2, q, k2, v2, slot, nn))
+    k_new = W.round_to_bits(RNG.standard_normal((B, Hkv, d)), "bf16")
+    v_new = W.round_to_bits(RNG.standard_normal((B, Hkv, d)), "bf16")
+    pos = np.array([9, 15], dtype=np.int32)          # middle of a block, last row of the last block
+    assert O.kv_append(p, k, v, k_new, v_new, slot, pos) == 0
+    assert O.kv_append(p2, k2, v2, k_new, v_new, slot, pos) == 0
+    assert np.array_equal(to_blocked(k), k2) and np.array_equal(to_blocked(v), v2)
+
+
 # ---------------------------------------------------------------- brute force
 def _brute(qv, K, V, scale):
     """Every term written out with math.exp; no max subtraction; column-major loop order."""
