@@ -205,6 +205,103 @@ __device__ __forceinline__ void keep_real_heads(u32x4 (&dst)[4], const u32x4 (&s
   for (int kk = 0; kk < 4; ++kk) dst[kk] = hn < nh ? src[kk] : u32x4{0u, 0u, 0u, 0u};
 }
 
+// Raw buffer descriptor word 3 for 32-bit raw access on this architecture, and the cache-policy
+// operand of buffer instructions: bit 0 = sc0, bit 1 = nt, bit 4 = sc1.
+constexpr int kRawBufferFlags = 0x00020000;
+constexpr int kWriteThrough = 0x11;
+
+// Exchange between lanes that differ in one bit of the lane number: afterwards the lanes with
+// that bit clear hold in `hi` what their partner had in `lo`, and the lanes with the bit set hold
+// in `lo` what their partner had in `hi` (the other halves stay).  No selects: the data parallel
+// primitives write only the enabled banks (bank = 4 lanes) or rows (row = 16 lanes).
+__device__ __forceinline__ void swap_lane_bit2(f32x4& lo, f32x4& hi) {
+#pragma unroll
+  for (int e = 0; e < 4; ++e) {
+    const int l = __float_as_int(lo[e]), h = __float_as_int(hi[e]);
+    // banks 0 and 2 (bit clear) read the lane 4 above, banks 1 and 3 the lane 4 below
+    hi[e] = __int_as_float(__builtin_amdgcn_update_dpp(h, l, 0x12c /*row_ror:12*/, 0xf, 0x5, false));
+    lo[e] = __int_as_float(__builtin_amdgcn_update_dpp(l, h, 0x124 /*row_ror:4*/, 0xf, 0xa, false));
+  }
+}
+__device__ __forceinline__ void swap_lane_bit3(f32x4& lo, f32x4& hi) {
+#pragma unroll
+  for (int e = 0; e < 4; ++e) {
+    const int l = __float_as_int(lo[e]), h = __float_as_int(hi[e]);
+    hi[e] = __int_as_float(__builtin_amdgcn_update_dpp(h, l, 0x128 /*row_ror:8*/, 0xf, 0x3, false));
+    lo[e] = __int_as_float(__builtin_amdgcn_update_dpp(l, h, 0x128 /*row_ror:8*/, 0xf, 0xc, false));
+  }
+}
+__device__ __forceinline__ void swap_lane_bit4(f32x4& lo, f32x4& hi) {
+  typedef uint32_t u32x2 __attribute__((ext_vector_type(2)));
+#pragma unroll
+  for (int e = 0; e < 4; ++e) {
+    // odd rows of the first operand trade places with even rows of the second
+    const u32x2 r = __builtin_amdgcn_permlane16_swap(__float_as_uint(lo[e]), __float_as_uint(hi[e]),
+                                                     false, false);
+    lo[e] = __uint_as_float(r[0]);
+    hi[e] = __uint_as_float(r[1]);
+  }
+}
+
+// Writes the running state as partial record `slot` of heads h0 .. h0+nh-1 of sequence b.
+//
+// Record stores are the expensive part of a strip border: on a ragged batch they are 0.5% of the
+// bytes and cost 10% of the kernel's time when written with plain stores (measured by leaving them
+// out), because every line written interrupts the read stream in memory.  Two measures, which only
+// help together (measured: 76% of peak bandwidth with either alone, 81% with both):
+//  * whole lines.  Lane (hn, c) holds columns 32c .. 32c+31 of head hn as eight 16-byte chunks;
+//    stored as they are, one instruction would put 16 bytes into each of 64 different cache lines.
+//    Three exchange stages trade the chunk index for lane bits 2, 3 and 4 instead: afterwards lane
+//    L, register r = r0 + 2 r1 + 4 r2 holds
+//        head   (L & 3) + 4 r0 + 8 r1,    chunk  (L >> 2) & 7  of column block  r2 + 2 (L >> 5),
+//    so the eight lanes that differ in bits 2-4 write one whole 128-byte line per instruction;
+//  * write-through stores (see below).
+__device__ __forceinline__ void store_record(const AttnArgs& a, int b, int h0, int nh, int slot,
+                                             const f32x4 (&acc)[8], float m, float l, int hn, int c) {
+  l += xor16(l);                       // the four lanes of a head share m; add their partial sums
+  l += xor32(l);
+  f32x4 x[8];                          // chunk q = columns 32c + 4q .. 32c + 4q + 3
+#pragma unroll
+  for (int i = 0; i < 4; ++i) {
+    // register i of column tile t is column 32c + 8i + t
+    x[2 * i] = f32x4{acc[0][i], acc[1][i], acc[2][i], acc[3][i]};
+    x[2 * i + 1] = f32x4{acc[4][i], acc[5][i], acc[6][i], acc[7][i]};
+  }
+#pragma unroll
+  for (int q = 0; q < 8; q += 2) swap_lane_bit2(x[q], x[q + 1]);
+#pragma unroll
+  for (int q = 0; q < 8; ++q)
+    if (!(q & 2)) swap_lane_bit3(x[q], x[q + 2]);
+#pragma unroll
+  for (int q = 0; q < 4; ++q) swap_lane_bit4(x[q], x[q + 4]);
+
+  // Write-through stores (sc0 sc1): among the store policies this one disturbs the read stream
+  // least (a streaming-read probe that writes 4 KiB per wave now and then: 7.0 TB/s without stores,
+  // 6.3 with plain stores, 6.6-6.7 with write-through or non-temporal ones), and unlike the
+  // non-temporal policy it leaves the records in cache for the merge kernel.  The policy bits are
+  // only reachable through buffer instructions, so the record of the wave's first head becomes the
+  // buffer base; its range ends with the last real head, and b, h0 and slot are wave-uniform.
+  const int lane = 16 * c + hn;
+  const int64_t head_pitch = (int64_t)a.n_chunks * kHeadDim;             // floats between heads
+  float* base = a.ws_o + (((int64_t)b * a.n_q_heads + h0) * a.n_chunks + slot) * kHeadDim;
+  const __amdgpu_buffer_rsrc_t rec = __builtin_amdgcn_make_buffer_rsrc(
+      base, 0, (int)(((nh - 1) * head_pitch + kHeadDim) * 4), kRawBufferFlags);
+  const int col = 64 * (lane >> 5) + 4 * ((lane >> 2) & 7);
+#pragma unroll
+  for (int r = 0; r < 8; ++r) {
+    const int head = (lane & 3) + 4 * (r & 3);
+    if (head < nh)
+      __builtin_amdgcn_raw_buffer_store_b128(
+          __builtin_bit_cast(u32x4, x[r]), rec,
+          (int)((head * head_pitch + col + 32 * (r >> 2)) * 4), 0, kWriteThrough);
+  }
+  if (hn < nh && c == 0) {
+    const int64_t pi = ((int64_t)b * a.n_q_heads + h0 + hn) * a.n_chunks + slot;
+    a.ws_m[pi] = m;
+    a.ws_l[pi] = l;
+  }
+}
+
 // Rows [r0, r1) (r0 < r1) of one strip for the heads h0 .. h0+nh-1 of sequence b, written as
 // partial record `slot` of those heads.
 template <bool BF16>
@@ -238,25 +335,7 @@ __device__ __forceinline__ void run_strip(const AttnArgs& a, int b, int h0, int 
     if (row0 + 32 < r1) process_tile<BF16>(tb, qop, acc, m, l, a.scale_log2e, row0 + 32, r1, c);
   }
 
-  // The four lanes of a head share m; add up their partial sums.
-  l += xor16(l);
-  l += xor32(l);
-  if (hn < nh) {
-    const int64_t pi = ((int64_t)b * a.n_q_heads + h0 + hn) * a.n_chunks + slot;
-    float* op = a.ws_o + pi * kHeadDim + 32 * c;
-#pragma unroll
-    for (int i = 0; i < 4; ++i) {
-      // register i of column tile t is column 32c + 8i + t
-      const float4 x0 = make_float4(acc[0][i], acc[1][i], acc[2][i], acc[3][i]);
-      const float4 x1 = make_float4(acc[4][i], acc[5][i], acc[6][i], acc[7][i]);
-      *reinterpret_cast<float4*>(op + 8 * i) = x0;
-      *reinterpret_cast<float4*>(op + 8 * i + 4) = x1;
-    }
-    if (c == 0) {
-      a.ws_m[pi] = m;
-      a.ws_l[pi] = l;
-    }
-  }
+  store_record(a, b, h0, nh, slot, acc, m, l, hn, c);
 }
 
 // Marks partial records [slot0, slot1) of heads h0 .. h0+nh-1 of sequence b as empty.
@@ -282,29 +361,6 @@ __global__ __launch_bounds__(64, 2) void attn_mfma_kernel(const AttnArgs a) {
     return;
   }
   run_strip<BF16>(a, it.b, it.h0, it.nh, it.strip, it.r0, it.r1, it.chunk, lane);
-}
-
-// Writes the running state as partial record `slot` of heads h0 .. h0+nh-1 of sequence b.
-__device__ __forceinline__ void store_record(const AttnArgs& a, int b, int h0, int nh, int slot,
-                                             const f32x4 (&acc)[8], float m, float l, int hn, int c) {
-  l += xor16(l);                       // the four lanes of a head share m; add their partial sums
-  l += xor32(l);
-  if (hn < nh) {
-    const int64_t pi = ((int64_t)b * a.n_q_heads + h0 + hn) * a.n_chunks + slot;
-    float* op = a.ws_o + pi * kHeadDim + 32 * c;
-#pragma unroll
-    for (int i = 0; i < 4; ++i) {
-      // register i of column tile t is column 32c + 8i + t
-      const float4 x0 = make_float4(acc[0][i], acc[1][i], acc[2][i], acc[3][i]);
-      const float4 x1 = make_float4(acc[4][i], acc[5][i], acc[6][i], acc[7][i]);
-      *reinterpret_cast<float4*>(op + 8 * i) = x0;
-      *reinterpret_cast<float4*>(op + 8 * i + 4) = x1;
-    }
-    if (c == 0) {
-      a.ws_m[pi] = m;
-      a.ws_l[pi] = l;
-    }
-  }
 }
 
 // Balanced split.  All strips (sequence, kv head, head pass) are laid end to end in units of
