@@ -96,6 +96,9 @@ def main():
                     help="order of a page's rows: [row][kv head] or [kv head][row]")
     ap.add_argument("--virtual-capacity", type=int, default=0,
                     help="rows per virtual slot in --paged mode (default: 3x the mean context)")
+    ap.add_argument("--graph", action="store_true",
+                    help="also time the step replayed from a HIP graph (one step per graph); the "
+                         "JSON line keeps the eager figures and adds config.hip_graph_ms_per_step")
     ap.add_argument("--pmc-calibration", action="store_true",
                     help="also run one plain 1 GiB device copy, the known-size kernel that "
                          "rocprofv3 FETCH_SIZE / WRITE_SIZE readings are scaled by")
@@ -216,6 +219,23 @@ def main():
         f"whole step {step_bytes / (elapsed / args.steps) / 1e9:.0f} GB/s | "
         f"{flops / attn_avg_s / 1e12:.1f} TFLOP/s algorithmic")
 
+    graph_ms = None
+    if args.graph:
+        # the three calls only launch kernels (no allocation, no memset, nothing read back), so a
+        # step is captured as it is; lengths and slots stay device arrays the replay re-reads
+        g = torch.cuda.CUDAGraph()
+        with torch.cuda.graph(g):
+            step()
+        for _ in range(args.warmup):
+            g.replay()
+        torch.cuda.synchronize()
+        t0 = time.perf_counter()
+        for _ in range(args.steps):
+            g.replay()
+        torch.cuda.synchronize()
+        graph_ms = (time.perf_counter() - t0) / args.steps * 1e3
+        log(f"HIP graph replay: {graph_ms:.4f} ms per step (eager {ms_per_step:.4f})")
+
     result = {
         "metric": "decode-attention sequence-steps/sec (achieved HBM GB/s and % of peak under roofline)",
         "value": w.batch * args.steps / elapsed,
@@ -229,7 +249,7 @@ def main():
                                f"seed={w.seed}",
                    "kernel": args.kernel, "chunk_rows": chunk_rows, "n_chunks": n_chunks,
                    "step": "gh_kv_append + gh_decode_attention + gh_decode_reduce",
-                   "paged_slots": paged_info,
+                   "paged_slots": paged_info, "hip_graph_ms_per_step": graph_ms,
                    "step_algorithmic_bytes": step_bytes,
                    "step_GBps": step_bytes / (elapsed / args.steps) / 1e9},
         "roofline": {"bound": "hbm", "kernel": "gh_decode_attention",

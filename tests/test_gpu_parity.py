@@ -426,3 +426,54 @@ def test_full_size_workload_sampled_sequences(name, n_samples):
           f"chunk_rows={G.gh_decode_chunk_rows(p)}")
     # properties that hold at any size: every output is a convex combination of value rows
     assert np.abs(got).max() < 8.0
+
+
+# ------------------------------------------------------------------ HIP graph replay
+@pytest.mark.parametrize("kernel", ["valu", "mfma"])
+def test_step_captured_in_a_hip_graph_replays_with_new_inputs(kernel):
+    """The three calls only launch kernels, and everything that changes from token to token
+    (lengths, positions, q, the new rows) lives in device arrays: a step captured once must give
+    the oracle's result on every replay after those arrays were rewritten in place.  Eager work
+    (poisoning the workspace and the output) and synchronisation sit between the replays."""
+    w = small("graph", 6, 8, 2, "bf16", 90)
+    L = np.array([0, 30, 31, 95, 200, 333], dtype=np.int32)
+    inp = W.make_inputs(w, DEV, lengths=L, n_slots=7, capacity=400)
+    host = Hh.host_copy(inp)
+    p = G.problem_from_inputs(inp, max_ctx_len=400, kernel=KERNELS[kernel])
+    ws = G.alloc_workspace(p, DEV)
+    out = torch.empty((w.batch, w.n_q_heads, w.head_dim), dtype=torch.float32, device=DEV)
+    status = torch.zeros(1, dtype=torch.int32, device=DEV)
+    G.decode_step(p, inp, ws, out, dev_status=status)          # eager once: code objects are loaded
+    torch.cuda.synchronize()
+    Hh.assert_parity(out.cpu().numpy(), Hh.oracle_step(inp, host), "eager")
+
+    g = torch.cuda.CUDAGraph()
+    with torch.cuda.graph(g):
+        G.decode_step(p, inp, ws, out, dev_status=status)
+    gen = torch.Generator(device=DEV)
+    gen.manual_seed(91)
+    for replay in range(4):
+        pos = L + 1 + 17 * replay                               # sequences grow by 17 rows a replay
+        for name in ("q", "k_new", "v_new"):                   # new token, written in place
+            inp[name].copy_(torch.randn(inp[name].shape, generator=gen, device=DEV).to(inp[name].dtype))
+            host[name] = W.bits(inp[name])
+        # rows [old length, pos) were never appended: give them values on both sides
+        for b in range(w.batch):
+            s, lo, hi = int(inp["slots"][b]), int(host["pos"][b]) + 1, int(pos[b])
+            for which in ("k_cache", "v_cache"):
+                fill = torch.randn((w.n_kv_heads, hi - lo, w.head_dim), generator=gen,
+                                   device=DEV).to(inp[which].dtype)
+                inp[which][s, :, lo:hi] = fill
+                host[which][s, :, lo:hi] = W.bits(fill)
+        inp["pos"].copy_(torch.from_numpy(pos.astype(np.int32)))
+        inp["ctx_len"].copy_(torch.from_numpy((pos + 1).astype(np.int32)))
+        host["pos"], host["ctx_len"] = pos.astype(np.int32), (pos + 1).astype(np.int32)
+        ws.fill_(float("nan"))
+        out.fill_(float("nan"))
+        torch.cuda.synchronize()
+        g.replay()
+        torch.cuda.synchronize()
+        Hh.assert_parity(out.cpu().numpy(), Hh.oracle_step(inp, host), f"replay {replay}")
+        assert status.item() == 0
+    assert np.array_equal(W.bits(inp["k_cache"]), host["k_cache"])
+
