@@ -20,71 +20,103 @@ __device__ __forceinline__ float wave_max(float x) {
   return x;
 }
 
-// One wave per (sequence, head); a lane owns two adjacent columns.  The (m, l) of the records
-// are read 64 at a time, one per lane, to find the common maximum and the weights; the o rows
-// are then accumulated in record order with independent loads, so the result does not depend on
-// scheduling.
+// One wave per (sequence, head); a lane owns two adjacent columns.  Heads with at most two records
+// take a short path on prefetched values; otherwise the (m, l) of the records are read 64 at a
+// time, one per lane, to find the common maximum and the weights, and the o rows are accumulated in
+// record order with independent loads.  Either way the order of the arithmetic is fixed, so the
+// result does not depend on scheduling.
 // OUT: 0 = fp32, 1 = binary16, 2 = bfloat16 (round to nearest even at the store).
 template <int OUT>
 __global__ __launch_bounds__(256) void decode_reduce_kernel(const ReduceArgs a) {
   const int lane = threadIdx.x & 63;
   const int64_t row = (int64_t)blockIdx.x * 4 + (threadIdx.x >> 6);
   if (row >= a.n_rows) return;
-  int used = a.ws_n[row];
-  used = used < 0 ? 0 : used < a.n_chunks ? used : a.n_chunks;
   const float* m = a.ws_m + row * a.n_chunks;
   const float* l = a.ws_l + row * a.n_chunks;
   const float* o = a.ws_o + row * a.n_chunks * kHeadDim + 2 * lane;
 
-  float M = kNegInf;
-  for (int c0 = 0; c0 < used; c0 += 64) {
-    const int c = c0 + lane;
-    const float lc = c < used ? l[c] : 0.f;
-    const float mc = c < used ? m[c] : kNegInf;
-    M = fmaxf(M, lc > 0.f ? mc : kNegInf);     // a record without rows carries no maximum
-  }
-  M = wave_max(M);
+  // The first two records are fetched before the count is known: they exist in the layout whatever
+  // the count says, most heads use one or two, and the count, the headers and the rows then cost
+  // one memory round trip instead of three.  What a record beyond the count holds is never used.
+  const bool two = a.n_chunks > 1;
+  const float2 o0 = *reinterpret_cast<const float2*>(o);
+  const float2 o1 = two ? *reinterpret_cast<const float2*>(o + kHeadDim) : make_float2(0.f, 0.f);
+  const float m0 = m[0], l0 = l[0];
+  const float m1 = two ? m[1] : kNegInf, l1 = two ? l[1] : 0.f;
+  int used = a.ws_n[row];
+  used = used < 0 ? 0 : used < a.n_chunks ? used : a.n_chunks;
 
   float2 acc = make_float2(0.f, 0.f);
-  float L = 0.f;
-  if (M != kNegInf) {
+  if (used <= 2) {
+    const float la = used > 0 ? l0 : 0.f, lb = used > 1 ? l1 : 0.f;
+    const float ma = la > 0.f ? m0 : kNegInf, mb = lb > 0.f ? m1 : kNegInf;
+    const float M = fmaxf(ma, mb);
+    if (M != kNegInf) {
+      const float wa = la > 0.f ? fast_exp2(ma - M) : 0.f;
+      const float wb = lb > 0.f ? fast_exp2(mb - M) : 0.f;
+      float L = 0.f;
+      if (wa > 0.f) {
+        acc.x = fmaf(wa, o0.x, acc.x);
+        acc.y = fmaf(wa, o0.y, acc.y);
+      }
+      L += wa * la;
+      if (wb > 0.f) {
+        acc.x = fmaf(wb, o1.x, acc.x);
+        acc.y = fmaf(wb, o1.y, acc.y);
+      }
+      L += wb * lb;
+      acc.x /= L;
+      acc.y /= L;
+    }
+  } else {
+    float M = kNegInf;
     for (int c0 = 0; c0 < used; c0 += 64) {
       const int c = c0 + lane;
       const float lc = c < used ? l[c] : 0.f;
       const float mc = c < used ? m[c] : kNegInf;
-      const float w = lc > 0.f ? fast_exp2(mc - M) : 0.f;   // this lane's record weight
-      const float wl = w * lc;
-      const int n = used - c0 < 64 ? used - c0 : 64;
-      int j = 0;
-      for (; j + 4 <= n; j += 4) {                           // four independent row loads
-        float2 oc[4];
-        float wj[4];
-#pragma unroll
-        for (int u = 0; u < 4; ++u) {
-          wj[u] = __shfl(w, j + u, 64);
-          oc[u] = *reinterpret_cast<const float2*>(o + (int64_t)(c0 + j + u) * kHeadDim);
-        }
-#pragma unroll
-        for (int u = 0; u < 4; ++u) {
-          if (wj[u] > 0.f) {                                 // an empty record's o is unspecified
-            acc.x = fmaf(wj[u], oc[u].x, acc.x);
-            acc.y = fmaf(wj[u], oc[u].y, acc.y);
-          }
-          L += __shfl(wl, j + u, 64);
-        }
-      }
-      for (; j < n; ++j) {
-        const float wj = __shfl(w, j, 64);
-        const float2 oc = *reinterpret_cast<const float2*>(o + (int64_t)(c0 + j) * kHeadDim);
-        if (wj > 0.f) {
-          acc.x = fmaf(wj, oc.x, acc.x);
-          acc.y = fmaf(wj, oc.y, acc.y);
-        }
-        L += __shfl(wl, j, 64);
-      }
+      M = fmaxf(M, lc > 0.f ? mc : kNegInf);     // a record without rows carries no maximum
     }
-    acc.x /= L;
-    acc.y /= L;
+    M = wave_max(M);
+    float L = 0.f;
+    if (M != kNegInf) {
+      for (int c0 = 0; c0 < used; c0 += 64) {
+        const int c = c0 + lane;
+        const float lc = c < used ? l[c] : 0.f;
+        const float mc = c < used ? m[c] : kNegInf;
+        const float w = lc > 0.f ? fast_exp2(mc - M) : 0.f;   // this lane's record weight
+        const float wl = w * lc;
+        const int n = used - c0 < 64 ? used - c0 : 64;
+        int j = 0;
+        for (; j + 4 <= n; j += 4) {                           // four independent row loads
+          float2 oc[4];
+          float wj[4];
+#pragma unroll
+          for (int u = 0; u < 4; ++u) {
+            wj[u] = __shfl(w, j + u, 64);
+            oc[u] = *reinterpret_cast<const float2*>(o + (int64_t)(c0 + j + u) * kHeadDim);
+          }
+#pragma unroll
+          for (int u = 0; u < 4; ++u) {
+            if (wj[u] > 0.f) {                                 // an empty record's o is unspecified
+              acc.x = fmaf(wj[u], oc[u].x, acc.x);
+              acc.y = fmaf(wj[u], oc[u].y, acc.y);
+            }
+            L += __shfl(wl, j + u, 64);
+          }
+        }
+        for (; j < n; ++j) {
+          const float wj = __shfl(w, j, 64);
+          const float2 oc = *reinterpret_cast<const float2*>(o + (int64_t)(c0 + j) * kHeadDim);
+          if (wj > 0.f) {
+            acc.x = fmaf(wj, oc.x, acc.x);
+            acc.y = fmaf(wj, oc.y, acc.y);
+          }
+          L += __shfl(wl, j, 64);
+        }
+      }
+      acc.x /= L;
+      acc.y /= L;
+    }
   }
   if constexpr (OUT == 0) {
     *reinterpret_cast<float2*>(static_cast<float*>(a.out) + row * kHeadDim + 2 * lane) = acc;
