@@ -428,6 +428,44 @@ def test_full_size_workload_sampled_sequences(name, n_samples):
     assert np.abs(got).max() < 8.0
 
 
+# ------------------------------------------------------------------ seeded sweep of odd shapes
+def test_seeded_sweep_of_shapes_layouts_and_splits():
+    """Forty seeded cases that mix what the other tests vary one at a time: batch size, head-group
+    size (up to two passes of 16 heads), length mixes with many empty and one-row sequences, spare
+    slots, the three cache layouts, both kernels, both splits, both dtypes."""
+    rng = np.random.default_rng(20250117)
+    for case in range(40):
+        B = int(rng.choice([1, 2, 3, 7, 33, 130, 300]))
+        Hkv = int(rng.choice([1, 2, 4]))
+        group = int(rng.choice([1, 2, 3, 4, 8, 16, 20, 32]))
+        kind = rng.integers(0, 4)
+        if kind == 0:
+            L = rng.integers(0, 3, size=B)                       # empty and one-row contexts
+        elif kind == 1:
+            L = rng.integers(0, 200, size=B)
+        elif kind == 2:
+            L = np.where(rng.random(B) < 0.5, 0, rng.integers(0, 700, size=B))
+        else:
+            L = rng.integers(28, 36, size=B) * int(rng.integers(1, 12))   # around tile borders
+        L = L.astype(np.int32)
+        if B * Hkv * group * int(L.sum() + B) > 6_000_000:       # keep the oracle's work small
+            L = (L // 4).astype(np.int32)
+        layout = str(rng.choice(["head_major", "token_major", "head_blocked"]))
+        kernel = str(rng.choice(["valu", "mfma"]))
+        chunk_rows = int(rng.choice([0, 0, 64, 128]))
+        dtype = str(rng.choice(["f16", "bf16"]))
+        n_slots = B + int(rng.integers(0, 5))
+        print(f"case {case}: B={B} Hkv={Hkv} group={group} kind={kind} max L={int(L.max())} "
+              f"{layout} {kernel} chunk_rows={chunk_rows} {dtype} n_slots={n_slots}", flush=True)
+        w = W.Workload(f"sweep{case}", B, Hkv * group, Hkv, 128, dtype, ("const", 0), 7000 + case)
+        inp = W.make_inputs(w, DEV, lengths=L, n_slots=n_slots, layout=layout, block_rows=32)
+        host = Hh.host_copy(inp)
+        got, _, _ = run_gpu(inp, chunk_rows, KERNELS[kernel])
+        Hh.assert_parity(got, Hh.oracle_step(inp, host), f"sweep case {case}")
+        assert np.array_equal(W.bits(inp["k_cache"]), host["k_cache"])
+        assert np.array_equal(W.bits(inp["v_cache"]), host["v_cache"])
+
+
 # ------------------------------------------------------------------ HIP graph replay
 @pytest.mark.parametrize("kernel", ["valu", "mfma"])
 def test_step_captured_in_a_hip_graph_replays_with_new_inputs(kernel):
