@@ -62,7 +62,7 @@ def cpu_baseline(inp, target_s=12.0):
         O.decode_attention(p, q, kc, vc, sid, pos + 1)
         return time.perf_counter() - t0
 
-    S0 = min(B, 2)
+    S0 = min(B, 16)                      # one sequence per host thread: a fair rate estimate
     t_probe = run(S0)
     S = int(max(S0, min(B, round(S0 * target_s / max(t_probe, 1e-6)))))
     S = min(S, 512)
