@@ -89,6 +89,12 @@ def main():
     ap.add_argument("--mixed", type=int, default=0, metavar="T",
                     help="experiment: the last 2*T batch entries become two prefill chunks of T "
                          "tokens each (entries sharing a slot with consecutive positions)")
+    ap.add_argument("--prefill", type=int, default=0, metavar="T",
+                    help="experiment: the whole batch is B/T prefill chunks of T tokens each, every "
+                         "chunk on its own slot behind the cached rows the workload draws")
+    ap.add_argument("--group", type=int, default=0, metavar="T",
+                    help="experiment: declare tokens_per_group = T (rows kT..kT+T-1 share a slot); "
+                         "the GB/s printed then counts every row's K/V as if read separately")
     ap.add_argument("--paged", action="store_true",
                     help="keep the caches in a gh_slot_pool (virtual slots, pages mapped on demand)")
     ap.add_argument("--page-rows", type=int, default=1024)
@@ -142,6 +148,15 @@ def main():
             slots[first:first + T] = slots[first]
         import dataclasses
         w = dataclasses.replace(w, note=w.note + f" [EXPERIMENT: two {T}-token prefill chunks]")
+    if args.prefill:
+        T = args.prefill
+        assert w.batch % T == 0 and not args.mixed
+        base = W.draw_lengths(w)[: w.batch // T]
+        lengths = (np.repeat(base, T) + np.tile(np.arange(T), w.batch // T)).astype(np.int32)
+        slots = np.repeat(W.draw_slots(w, w.batch)[: w.batch // T], T)
+        import dataclasses
+        w = dataclasses.replace(w, note=w.note + f" [EXPERIMENT: {w.batch // T} prefill chunks of "
+                                                 f"{T} tokens, tokens_per_group={args.group}]")
     inp = W.make_inputs(w, "cuda", capacity=args.capacity or None, lengths=lengths, slots=slots,
                         layout="token_major" if args.paged else "head_major")
     torch.cuda.synchronize()
@@ -165,7 +180,8 @@ def main():
                       "layout": args.paged_layout + ", HIP virtual memory"}
         log(f"paged slots: {paged_info}")
     kernel = {"auto": G.GH_KERNEL_AUTO, "valu": G.GH_KERNEL_VALU, "mfma": G.GH_KERNEL_MFMA}[args.kernel]
-    p = G.problem_from_inputs(inp, chunk_rows=args.chunk_rows, kernel=kernel)
+    p = G.problem_from_inputs(inp, chunk_rows=args.chunk_rows, kernel=kernel,
+                              tokens_per_group=args.group)
     ws = G.alloc_workspace(p)
     out = torch.empty((w.batch, w.n_q_heads, w.head_dim), dtype=torch.float32, device="cuda")
     ctx = inp["lengths"].astype(np.int64) + 1
@@ -258,7 +274,7 @@ def main():
                      "traffic": args.traffic_bytes if args.traffic_bytes is not None else (
                          MEASURED_TRAFFIC_BYTES.get(w.name)
                          if args.kernel == "auto" and not (args.chunk_rows or args.batch or args.const_len or args.capacity or args.paged
-                                                      or args.mixed)
+                                                      or args.mixed or args.prefill or args.group)
                          else None),
                      "algorithmic_bytes_per_launch": attn_bytes,
                      "avg_launch_ms": float(attn_ms.mean())},

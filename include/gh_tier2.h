@@ -45,6 +45,20 @@
  *     rows [0, ctx_len) of its slot; since the append of the whole batch runs
  *     first, entry t of a chunk sees the chunk's earlier tokens and not the
  *     later ones: causal attention, with no other provision.
+ *   - Token groups (tokens_per_group = T > 1): an optional declaration that
+ *     lets the tokens of a prefill chunk share one pass over their slot.  Batch
+ *     rows kT .. kT+T-1 form group k and address one slot; each row keeps its
+ *     own ctx_len (and q, position, output row).  gh_decode_attention then
+ *     streams the slot's K/V rows once per group and kv head -- the T*G query
+ *     heads of a group fill the 16 head columns of a matrix-core tile, each
+ *     column masked at its own token's length -- instead of once per row.  A
+ *     row with ctx_len 0, a bad slot id, or a slot other than that of the
+ *     group's first live row gets no rows (output zero), so short groups are
+ *     padded with ctx_len = 0 rows and a decode entry is a group with one live
+ *     row.  Results are those of the undeclared batch up to fp32 rounding
+ *     order.  gh_kv_append and the merge are unaffected (they work per row).
+ *     Requires the matrix-core kernel with the library's split (chunk_rows = 0,
+ *     at most 4096 groups); anything else returns GH_ERR_UNSUPPORTED.
  */
 #ifndef GH_TIER2_H
 #define GH_TIER2_H
@@ -102,6 +116,9 @@ typedef struct {
                                straight out of one packed per-sequence message
                                q | k | v (Section 5.4.3: what Tier 1 sends).      */
   int32_t block_rows;       /* 0, or a power of two >= 32: blocked cache layout   */
+  int32_t tokens_per_group; /* T; 0 or 1: none.  T > 1 declares that batch rows
+                               kT .. kT+T-1 address one slot (see above); batch
+                               must be a multiple of T                            */
   int64_t block_stride;     /* elements between consecutive blocks of one head    */
 } gh_problem;
 

@@ -38,7 +38,7 @@ class gh_problem(C.Structure):
         ("slot_stride", C.c_int64), ("head_stride", C.c_int64), ("row_stride", C.c_int64),
         ("scale", C.c_float), ("chunk_rows", C.c_int32), ("kernel", C.c_int32),
         ("q_batch_stride", C.c_int64), ("new_batch_stride", C.c_int64),
-        ("block_rows", C.c_int32), ("block_stride", C.c_int64),
+        ("block_rows", C.c_int32), ("tokens_per_group", C.c_int32), ("block_stride", C.c_int64),
     ]
 
 
@@ -137,10 +137,11 @@ def _stream(stream):
 
 def make_problem(batch, n_q_heads, n_kv_heads, head_dim, dtype, n_slots, slot_capacity,
                  max_ctx_len, strides, scale, chunk_rows=0, kernel=GH_KERNEL_AUTO,
-                 q_batch_stride=0, new_batch_stride=0, block=(0, 0)):
+                 q_batch_stride=0, new_batch_stride=0, block=(0, 0), tokens_per_group=0):
     return gh_problem(batch, n_q_heads, n_kv_heads, head_dim, dtype, n_slots, slot_capacity,
                       max_ctx_len, strides[0], strides[1], strides[2], scale, chunk_rows, kernel,
-                      q_batch_stride, new_batch_stride, int(block[0]), int(block[1]))
+                      q_batch_stride, new_batch_stride, int(block[0]), int(tokens_per_group),
+                      int(block[1]))
 
 
 def gh_status_string(status):
@@ -188,7 +189,8 @@ def check(status):
         raise GhError(status)
 
 
-def problem_from_inputs(inp, chunk_rows=0, kernel=GH_KERNEL_AUTO, max_ctx_len=None):
+def problem_from_inputs(inp, chunk_rows=0, kernel=GH_KERNEL_AUTO, max_ctx_len=None,
+                        tokens_per_group=0):
     """gh_problem for a dict made by workloads.make_inputs."""
     w = inp["workload"]
     dtype = GH_BF16 if w.dtype == "bf16" else GH_F16
@@ -196,7 +198,7 @@ def problem_from_inputs(inp, chunk_rows=0, kernel=GH_KERNEL_AUTO, max_ctx_len=No
         max_ctx_len = int(inp["lengths"].max()) + 1
     return make_problem(w.batch, w.n_q_heads, w.n_kv_heads, w.head_dim, dtype, inp["n_slots"],
                         inp["capacity"], max_ctx_len, inp["strides"], inp["scale"], chunk_rows,
-                        kernel, block=inp.get("block", (0, 0)))
+                        kernel, block=inp.get("block", (0, 0)), tokens_per_group=tokens_per_group)
 
 
 def alloc_workspace(p, device="cuda"):

@@ -119,10 +119,13 @@ __device__ __forceinline__ void load_tile(TileRegs& t, const uint16_t* kbase, co
   }
 }
 
+// One 32-row tile for the 16 head columns.  `lim` is the number of rows the lane's head column
+// attends (rows at or beyond it are masked); columns of one tile may have different limits, and a
+// column may have no row at all in a tile.
 template <bool BF16>
 __device__ __forceinline__ void process_tile(const TileRegs& t, const u32x4 (&qop)[4], f32x4 (&acc)[8],
                                              float& m, float& l, float scale_log2e, int tile_row0,
-                                             int r1, int c) {
+                                             int lim, int c) {
   // scores of head hn against this lane's 8 rows
   f32x4 s[2];
 #pragma unroll
@@ -142,19 +145,22 @@ __device__ __forceinline__ void process_tile(const TileRegs& t, const u32x4 (&qo
 #pragma unroll
   for (int e = 0; e < 8; ++e) {
     const int row = tile_row0 + 16 * (e >> 2) + 4 * (e & 3) + c;
-    tv[e] = row < r1 ? s[e >> 2][e & 3] * scale_log2e : kNegInf;
+    tv[e] = row < lim ? s[e >> 2][e & 3] * scale_log2e : kNegInf;
     mx = fmaxf(mx, tv[e]);
   }
   mx = fmaxf(mx, xor16(mx));
-  mx = fmaxf(mx, xor32(mx));           // the tile has at least one row, so mx is finite
+  mx = fmaxf(mx, xor32(mx));
   const float mn = fmaxf(m, mx);
-  const float alpha = fast_exp2(m - mn);
+  // a column that has seen no row yet keeps m = -inf; subtract 0 then, so that every exponent
+  // below is -inf (weight 0) rather than inf - inf
+  const float ref = mn == kNegInf ? 0.f : mn;
+  const float alpha = fast_exp2(m - ref);
   m = mn;
   float sum = 0.f;
   float lo[8];
 #pragma unroll
   for (int e = 0; e < 8; ++e) {
-    tv[e] = fast_exp2(tv[e] - mn);
+    tv[e] = fast_exp2(tv[e] - ref);
     sum += tv[e];
   }
   l = fmaf(l, alpha, sum);
@@ -188,16 +194,16 @@ __device__ __forceinline__ void process_tile(const TileRegs& t, const u32x4 (&qo
   }
 }
 
-// Loads the Q operand of heads h0 .. h0+nh-1 of sequence b.  Padding lanes (hn >= nh) load head
-// h0 as well -- the load is unconditional so that nothing has to wait for it at the point of
-// issue -- and are zeroed by keep_real_heads() when the operand is taken into use.
-__device__ __forceinline__ void load_q(u32x4 (&qop)[4], const AttnArgs& a, int b, int h0, int nh,
-                                       int hn, int c) {
-  const int head = h0 + (hn < nh ? hn : 0);
+// Loads the Q operand of the nh head columns of pass `pass` of kv head g in group b.  Padding lanes
+// (hn >= nh) load column 0 as well -- the load is unconditional so that nothing has to wait for it
+// at the point of issue -- and are zeroed by keep_real_heads() when the operand is taken into use.
+__device__ __forceinline__ void load_q(u32x4 (&qop)[4], const AttnArgs& a, int b, int g, int pass,
+                                       int nh, int hn, int c) {
+  const Column x = column_of(a, b, g, pass, hn < nh ? hn : 0);
 #pragma unroll
   for (int kk = 0; kk < 4; ++kk)
     qop[kk] = *reinterpret_cast<const u32x4*>(
-        a.q + (int64_t)b * a.q_batch_stride + head * kHeadDim + 32 * kk + 8 * c);
+        a.q + x.token_row * a.q_batch_stride + x.head * kHeadDim + 32 * kk + 8 * c);
 }
 __device__ __forceinline__ void keep_real_heads(u32x4 (&dst)[4], const u32x4 (&src)[4], int nh,
                                                 int hn) {
@@ -256,8 +262,9 @@ __device__ __forceinline__ void swap_lane_bit4(f32x4& lo, f32x4& hi) {
 //        head   (L & 3) + 4 r0 + 8 r1,    chunk  (L >> 2) & 7  of column block  r2 + 2 (L >> 5),
 //    so the eight lanes that differ in bits 2-4 write one whole 128-byte line per instruction;
 //  * write-through stores (see below).
-__device__ __forceinline__ void store_record(const AttnArgs& a, int b, int h0, int nh, int slot,
-                                             const f32x4 (&acc)[8], float m, float l, int hn, int c) {
+__device__ __forceinline__ void store_record(const AttnArgs& a, int b, int g, int pass, int nh,
+                                             int slot, const f32x4 (&acc)[8], float m, float l,
+                                             int hn, int c) {
   l += xor16(l);                       // the four lanes of a head share m; add their partial sums
   l += xor32(l);
   f32x4 x[8];                          // chunk q = columns 32c + 4q .. 32c + 4q + 3
@@ -280,23 +287,29 @@ __device__ __forceinline__ void store_record(const AttnArgs& a, int b, int h0, i
   // 6.3 with plain stores, 6.6-6.7 with write-through or non-temporal ones), and unlike the
   // non-temporal policy it leaves the records in cache for the merge kernel.  The policy bits are
   // only reachable through buffer instructions, so the record of the wave's first head becomes the
-  // buffer base; its range ends with the last real head, and b, h0 and slot are wave-uniform.
+  // buffer base; its range ends with the last real column (the columns' records lie at increasing
+  // addresses), and b, g, pass and slot are wave-uniform.
   const int lane = 16 * c + hn;
-  const int64_t head_pitch = (int64_t)a.n_chunks * kHeadDim;             // floats between heads
-  float* base = a.ws_o + (((int64_t)b * a.n_q_heads + h0) * a.n_chunks + slot) * kHeadDim;
+  const int64_t pitch = (int64_t)a.n_chunks * kHeadDim;      // floats between (token row, head) pairs
+  const int64_t first = column_index(a, b, g, pass, 0);
+  const int64_t last = column_index(a, b, g, pass, nh - 1);
+  float* base = a.ws_o + (first * a.n_chunks + slot) * kHeadDim;
   const __amdgpu_buffer_rsrc_t rec = __builtin_amdgcn_make_buffer_rsrc(
-      base, 0, (int)(((nh - 1) * head_pitch + kHeadDim) * 4), kRawBufferFlags);
+      base, 0, (int)(((last - first) * pitch + kHeadDim) * 4), kRawBufferFlags);
   const int col = 64 * (lane >> 5) + 4 * ((lane >> 2) & 7);
 #pragma unroll
-  for (int r = 0; r < 8; ++r) {
-    const int head = (lane & 3) + 4 * (r & 3);
-    if (head < nh)
-      __builtin_amdgcn_raw_buffer_store_b128(
-          __builtin_bit_cast(u32x4, x[r]), rec,
-          (int)((head * head_pitch + col + 32 * (r >> 2)) * 4), 0, kWriteThrough);
+  for (int k = 0; k < 4; ++k) {
+    const int head = (lane & 3) + 4 * k;                     // head column of registers k and k + 4
+    if (head < nh) {
+      const int at = (int)(((column_index(a, b, g, pass, head) - first) * pitch + col) * 4);
+      __builtin_amdgcn_raw_buffer_store_b128(__builtin_bit_cast(u32x4, x[k]), rec, at, 0,
+                                             kWriteThrough);
+      __builtin_amdgcn_raw_buffer_store_b128(__builtin_bit_cast(u32x4, x[k + 4]), rec, at + 32 * 4,
+                                             0, kWriteThrough);
+    }
   }
   if (hn < nh && c == 0) {
-    const int64_t pi = ((int64_t)b * a.n_q_heads + h0 + hn) * a.n_chunks + slot;
+    const int64_t pi = column_index(a, b, g, pass, hn) * a.n_chunks + slot;
     a.ws_m[pi] = m;
     a.ws_l[pi] = l;
   }
@@ -305,13 +318,13 @@ __device__ __forceinline__ void store_record(const AttnArgs& a, int b, int h0, i
 // Rows [r0, r1) (r0 < r1) of one strip for the heads h0 .. h0+nh-1 of sequence b, written as
 // partial record `slot` of those heads.
 template <bool BF16>
-__device__ __forceinline__ void run_strip(const AttnArgs& a, int b, int h0, int nh, int64_t strip,
-                                          int r0, int r1, int slot, int lane) {
+__device__ __forceinline__ void run_strip(const AttnArgs& a, int b, int g, int pass, int nh,
+                                          int64_t strip, int r0, int r1, int slot, int lane) {
   const int hn = lane & 15, c = lane >> 4;
 
   // Q operand: d-chunk 4kk + c of head hn (zeros for the padding heads).
   u32x4 qraw[4], qop[4];
-  load_q(qraw, a, b, h0, nh, hn, c);
+  load_q(qraw, a, b, g, pass, nh, hn, c);
   keep_real_heads(qop, qraw, nh, hn);
 
   f32x4 acc[8];
@@ -335,7 +348,7 @@ __device__ __forceinline__ void run_strip(const AttnArgs& a, int b, int h0, int 
     if (row0 + 32 < r1) process_tile<BF16>(tb, qop, acc, m, l, a.scale_log2e, row0 + 32, r1, c);
   }
 
-  store_record(a, b, h0, nh, slot, acc, m, l, hn, c);
+  store_record(a, b, g, pass, nh, slot, acc, m, l, hn, c);
 }
 
 // Marks partial records [slot0, slot1) of heads h0 .. h0+nh-1 of sequence b as empty.
@@ -360,7 +373,7 @@ __global__ __launch_bounds__(64, 2) void attn_mfma_kernel(const AttnArgs a) {
     mark_empty(a, it.b, it.h0, it.nh, it.chunk, it.chunk + 1, lane);
     return;
   }
-  run_strip<BF16>(a, it.b, it.h0, it.nh, it.strip, it.r0, it.r1, it.chunk, lane);
+  run_strip<BF16>(a, it.b, it.g, it.pass, it.nh, it.strip, it.r0, it.r1, it.chunk, lane);
 }
 
 // Balanced split.  All strips (sequence, kv head, head pass) are laid end to end in units of
@@ -375,9 +388,15 @@ __global__ __launch_bounds__(64, 2) void attn_mfma_kernel(const AttnArgs a) {
 // strip is fetched one strip ahead.  (Draining the stream at every strip border cost about 20 us
 // per border under load -- three dependent memory round trips.)
 //
-// Dynamic LDS, three arrays indexed by sequence: cum[B + 1] = tiles of all strips of earlier
-// sequences (all strips of a sequence have the same number of tiles), rows[B] = rows attended
-// (0 for a sequence that is skipped), base[B] = slot id (0 for a skipped sequence).
+// A group is T consecutive token rows of the batch that address one slot (T = 1: one sequence).
+// Its strips stream the rows the longest of its tokens attends; each head column of a tile belongs
+// to one token and is masked at that token's own length, so the K/V rows of a prefill chunk are
+// read once for T tokens.  Token rows that are empty, invalid or on another slot than the group's
+// first live row get no rows (their output is zero).
+//
+// Dynamic LDS, three arrays indexed by group: cum[B + 1] = tiles of all strips of earlier groups
+// (all strips of a group have the same number of tiles), rows[B] = rows streamed (0 for a group
+// without a live token), base[B] = slot id (0 for such a group).
 struct TileCursor {
   uint32_t t;       // global tile index
   int b;            // sequence
@@ -388,7 +407,7 @@ struct TileCursor {
   int slot;         // cache slot (0 when n == 0)
 };
 
-template <bool BF16>
+template <bool BF16, bool GROUPED>
 __global__ __launch_bounds__(256, 2) void attn_mfma_balanced_kernel(const AttnArgs a) {
   extern __shared__ uint32_t lds[];
   __shared__ uint32_t part[256];
@@ -400,11 +419,15 @@ __global__ __launch_bounds__(256, 2) void attn_mfma_balanced_kernel(const AttnAr
   const uint32_t spb = (uint32_t)(a.n_kv_heads * a.n_pass);   // strips per sequence
 
   for (int b = tid; b < B; b += 256) {
-    int slot = a.slot_id[b];
-    int n = a.ctx_len[b];
-    n = n < a.row_limit ? n : a.row_limit;
-    if (slot < 0 || slot >= a.n_slots || n < 0) n = 0;
-    if (n == 0) slot = 0;
+    int slot = 0, n = 0;
+    for (int t = 0; t < a.tokens; ++t) {
+      const int st = a.slot_id[(int64_t)b * a.tokens + t];
+      int nt = a.ctx_len[(int64_t)b * a.tokens + t];
+      nt = nt < a.row_limit ? nt : a.row_limit;
+      if (st < 0 || st >= a.n_slots || nt <= 0) continue;
+      if (n == 0) slot = st;                     // the first live token row names the group's slot
+      if (st == slot) n = nt > n ? nt : n;
+    }
     rows[b] = n;
     slots[b] = slot;
     cum[b + 1] = (n > 0 ? (uint32_t)(n + 31) >> 5 : 1u) * spb;
@@ -459,11 +482,31 @@ __global__ __launch_bounds__(256, 2) void attn_mfma_balanced_kernel(const AttnAr
       }
     }
   };
-  auto heads_of = [&](uint32_t sib, int& h0, int& nh) {
-    const int g = (int)(sib / (uint32_t)a.n_pass), pass = (int)(sib % (uint32_t)a.n_pass);
-    h0 = g * a.group + pass * a.heads_per_pass;
+  auto pass_of = [&](uint32_t sib, int& g, int& pass, int& nh) {
+    g = (int)(sib / (uint32_t)a.n_pass);
+    pass = (int)(sib % (uint32_t)a.n_pass);
     const int left = a.group - pass * a.heads_per_pass;
     nh = left < a.heads_per_pass ? left : a.heads_per_pass;
+  };
+  // Rows the lane's head column attends.  GROUPED (T > 1): the token row's own length if it is live
+  // and on the group's slot, loaded with the Q operand, unconditionally, and taken into use with
+  // it.  Otherwise it is the length of the strip's sequence, which the cursor already holds.
+  struct Limit { int slot, n; };
+  auto load_limit = [&](const TileCursor& cu, int b, int g, int pass, int nh) {
+    if constexpr (GROUPED) {
+      const int64_t row = column_of(a, b, g, pass, hn < nh ? hn : 0).token_row;
+      return Limit{a.slot_id[row], a.ctx_len[row]};
+    } else {
+      return Limit{cu.slot, cu.n};
+    }
+  };
+  auto rows_of = [&](const Limit& x, int slot) {
+    if constexpr (GROUPED) {
+      const int n = x.n < a.row_limit ? x.n : a.row_limit;
+      return x.slot == slot && n > 0 ? n : 0;
+    } else {
+      return x.n;
+    }
   };
   auto issue = [&](TileRegs& regs, const TileCursor& cu) {
     const int g = (int)(cu.sib / (uint32_t)a.n_pass);
@@ -507,18 +550,23 @@ __global__ __launch_bounds__(256, 2) void attn_mfma_balanced_kernel(const AttnAr
     }
   };
 
-  // qop: operand of the strip being computed; qnext: raw rows of the following strip, in flight
-  // for a whole strip before they are taken into use; qnext_nh: how many of its heads are real.
+  // qop, lim: operand and row limit of the strip being computed; qnext, lnext: raw rows and limit
+  // of the following strip, in flight for a whole strip before they are taken into use; qnext_nh:
+  // how many of its columns are real; lnext_slot: its group's slot.
   u32x4 qop[4], qnext[4];
-  int h0, nh, qnext_nh = 0;
-  heads_of(cp.sib, h0, nh);
-  load_q(qnext, a, cp.b, h0, nh, hn, c);
+  int g, pass, nh, qnext_nh = 0, lnext_slot = 0;
+  pass_of(cp.sib, g, pass, nh);
+  load_q(qnext, a, cp.b, g, pass, nh, hn, c);
+  Limit lnext = load_limit(cp, cp.b, g, pass, nh);
   keep_real_heads(qop, qnext, nh, hn);
+  int lim = rows_of(lnext, cp.slot);
   next_strip(qs);
   if (qs.t < t_end) {
-    int qh0;
-    heads_of(qs.sib, qh0, qnext_nh);
-    load_q(qnext, a, qs.b, qh0, qnext_nh, hn, c);
+    int qg, qpass;
+    pass_of(qs.sib, qg, qpass, qnext_nh);
+    load_q(qnext, a, qs.b, qg, qpass, qnext_nh, hn, c);
+    lnext = load_limit(qs, qs.b, qg, qpass, qnext_nh);
+    lnext_slot = qs.slot;
   }
 
   f32x4 acc[8];
@@ -529,31 +577,39 @@ __global__ __launch_bounds__(256, 2) void attn_mfma_balanced_kernel(const AttnAr
   // One tile of arithmetic; closes the record when the tile ends this wave's piece of the strip.
   auto compute = [&](const TileRegs& regs) {
     if (cp.n > 0)
-      process_tile<BF16>(regs, qop, acc, m, l, a.scale_log2e, (int)cp.lt * 32, cp.n, c);
+      process_tile<BF16>(regs, qop, acc, m, l, a.scale_log2e, (int)cp.lt * 32, lim, c);
     const bool strip_end = cp.lt + 1 == cp.tiles;
     if (strip_end || cp.t + 1 == t_end) {
       const uint32_t strip_t0 = cp.t - cp.lt;                  // global index of the strip's tile 0
       int rec = (int)(gw - strip_t0 / share);
-      heads_of(cp.sib, h0, nh);
+      pass_of(cp.sib, g, pass, nh);
       if (cp.n > 0) {
-        store_record(a, cp.b, h0, nh, rec, acc, m, l, hn, c);
+        store_record(a, cp.b, g, pass, nh, rec, acc, m, l, hn, c);
         ++rec;
       }
       if (strip_end && hn < nh && c == 0)                     // records in use for these heads
-        a.ws_n[(int64_t)cp.b * a.n_q_heads + h0 + hn] = rec;
+        a.ws_n[column_index(a, cp.b, g, pass, hn)] = rec;
       if (cp.t + 1 < t_end) {                                  // the next tile opens a strip
 #pragma unroll
         for (int tcol = 0; tcol < 8; ++tcol) acc[tcol] = f32x4{0.f, 0.f, 0.f, 0.f};
         m = kNegInf;
         l = 0.f;
         keep_real_heads(qop, qnext, qnext_nh, hn);
+        lim = rows_of(lnext, lnext_slot);
         next_strip(qs);
         {
           // unconditional: when no strip follows, this strip's rows are fetched again (unused)
           const bool more = qs.t < t_end;
-          int qh0;
-          heads_of(more ? qs.sib : cp.sib, qh0, qnext_nh);
-          load_q(qnext, a, more ? qs.b : cp.b, qh0, qnext_nh, hn, c);
+          const int qb = more ? qs.b : cp.b;
+          int qg, qpass;
+          pass_of(more ? qs.sib : cp.sib, qg, qpass, qnext_nh);
+          load_q(qnext, a, qb, qg, qpass, qnext_nh, hn, c);
+          if constexpr (GROUPED) {
+            lnext = load_limit(qs, qb, qg, qpass, qnext_nh);
+          } else {
+            lnext = Limit{0, more ? qs.n : cp.n};
+          }
+          lnext_slot = more ? qs.slot : cp.slot;
         }
       }
     }

@@ -24,7 +24,9 @@ struct AttnArgs {
   int64_t q_batch_stride;                         // elements between sequences in q
   int64_t block_stride;                           // blocked layout, see row_offset()
   int32_t block_shift, block_mask;                // log2(block_rows), block_rows - 1
-  int32_t n_q_heads, n_kv_heads, group;           // H, H_kv, G = H / H_kv
+  int32_t n_q_heads, n_kv_heads;                  // H, H_kv
+  int32_t tokens, real_group;                     // T token rows per group, G = H / H_kv
+  int32_t group;                                  // head columns per (group, kv head): T * G
   int32_t n_slots, row_limit;                     // row_limit = min(capacity, max_ctx_len)
   int32_t chunk_rows, n_chunks;
   int32_t heads_per_pass, n_pass;                 // head sub-groups of one kv head
@@ -40,6 +42,28 @@ struct AttnArgs {
 __device__ __forceinline__ int64_t row_offset(int r, int64_t row_stride, int64_t block_stride,
                                               int shift, int mask) {
   return (int64_t)(r >> shift) * block_stride + (int64_t)(r & mask) * row_stride;
+}
+
+// Head column `col` of pass `pass` of kv head g in group b: with (t, i) = divmod(pass * heads_per_pass
+// + col, G) it is query head g*G + i of token row b*T + t.  (T = 1: the group is one sequence and
+// the columns are the G heads of the kv head.)
+struct Column {
+  int64_t token_row;
+  int head;
+};
+__device__ __forceinline__ Column column_of(const AttnArgs& a, int b, int g, int pass, int col) {
+  const int cig = pass * a.heads_per_pass + col;
+  int t = 0, i = cig;
+  if (a.tokens > 1) {
+    t = cig / a.real_group;
+    i = cig - t * a.real_group;
+  }
+  return Column{(int64_t)b * a.tokens + t, g * a.real_group + i};
+}
+// Index of a column's (token row, head) pair in the [B, H] arrays of the workspace.
+__device__ __forceinline__ int64_t column_index(const AttnArgs& a, int b, int g, int pass, int col) {
+  const Column x = column_of(a, b, g, pass, col);
+  return x.token_row * a.n_q_heads + x.head;
 }
 
 // One unit of work: (sequence, kv head, head pass, chunk).  The chunk index

@@ -34,6 +34,11 @@ void block_params(const gh_problem* p, int64_t* stride, int32_t* shift, int32_t*
 bool aligned16(const void* p) { return (reinterpret_cast<uintptr_t>(p) & 15u) == 0; }
 
 // Everything about gh_problem that can be judged on the host.
+constexpr int kBalancedMaxBatch = 4096;     // three per-group arrays live in LDS (48 KB)
+constexpr int kMaxTokensPerGroup = 64;
+
+int tokens_per_group(const gh_problem* p) { return p->tokens_per_group > 1 ? p->tokens_per_group : 1; }
+
 int32_t check_problem(const gh_problem* p) {
   if (!p) return GH_ERR_NULL;
   if (p->batch < 0 || p->n_q_heads <= 0 || p->n_kv_heads <= 0 || p->n_slots <= 0 ||
@@ -52,6 +57,14 @@ int32_t check_problem(const gh_problem* p) {
   if (p->block_rows > 0 && (p->block_rows < 32 || (p->block_rows & (p->block_rows - 1)) != 0))
     return GH_ERR_UNSUPPORTED;
   if (p->block_rows > 0 && p->block_stride % 8) return GH_ERR_UNSUPPORTED;
+  if (p->tokens_per_group < 0) return GH_ERR_SHAPE;
+  if (p->tokens_per_group > 1) {
+    // groups run on the matrix-core kernel with the library's split only
+    if (p->batch % p->tokens_per_group != 0) return GH_ERR_SHAPE;
+    if (p->tokens_per_group > kMaxTokensPerGroup || p->kernel == GH_KERNEL_VALU ||
+        p->chunk_rows != 0 || p->batch / p->tokens_per_group > kBalancedMaxBatch)
+      return GH_ERR_UNSUPPORTED;
+  }
   if (p->q_batch_stride < 0 || p->new_batch_stride < 0) return GH_ERR_SHAPE;
   if (p->q_batch_stride % 8 || p->new_batch_stride % 8) return GH_ERR_UNSUPPORTED;
   if (p->q_batch_stride != 0 && p->q_batch_stride < (int64_t)p->n_q_heads * p->head_dim)
@@ -69,7 +82,8 @@ int resolve_kernel(const gh_problem* p) {
 
 // Heads of one kv head handled by a single work item, and how many such passes.
 void head_passes(const gh_problem* p, int kernel, int* per_pass, int* n_pass) {
-  const int group = p->n_q_heads / p->n_kv_heads;
+  // head columns of one (group, kv head): the G heads of each of the group's token rows
+  const int group = p->n_q_heads / p->n_kv_heads * tokens_per_group(p);
   int hp;
   if (kernel == GH_KERNEL_MFMA) {
     hp = 16;
@@ -102,7 +116,6 @@ struct Plan {
   int n_workers, min_share; // balanced split only
 };
 
-constexpr int kBalancedMaxBatch = 4096;     // three per-sequence arrays live in LDS (48 KB)
 constexpr int kBalancedWavesPerCU = 8;      // resident waves of the MFMA kernel per compute unit
 constexpr int kBalancedMaxRecords = 64;     // partial records per (sequence, head)
 
@@ -112,9 +125,10 @@ Plan make_plan(const gh_problem* p) {
   head_passes(p, pl.kernel, &pl.per_pass, &pl.n_pass);
   pl.balanced = false;
   pl.n_workers = pl.min_share = 0;
-  const int64_t strips = (int64_t)(p->batch > 0 ? p->batch : 1) * p->n_kv_heads * pl.n_pass;
+  const int groups = p->batch / tokens_per_group(p);
+  const int64_t strips = (int64_t)(groups > 0 ? groups : 1) * p->n_kv_heads * pl.n_pass;
   const int64_t max_tiles = p->max_ctx_len > 0 ? (p->max_ctx_len + 31) / 32 : 1;
-  if (pl.kernel == GH_KERNEL_MFMA && p->chunk_rows == 0 && p->batch <= kBalancedMaxBatch &&
+  if (pl.kernel == GH_KERNEL_MFMA && p->chunk_rows == 0 && groups <= kBalancedMaxBatch &&
       strips * max_tiles < 0x7fffffff) {
     // Records per head: enough for the longest strip when strips are up to four times the
     // average length; beyond that the share per wave grows instead (min_share).
@@ -226,6 +240,7 @@ int32_t gh_decode_attention(const gh_problem* p, const void* q, const void* k_ca
   if (!aligned16(q) || !aligned16(k_cache) || !aligned16(v_cache) || !aligned16(workspace))
     return GH_ERR_UNSUPPORTED;
   const Plan pl = make_plan(p);
+  if (tokens_per_group(p) > 1 && !pl.balanced) return GH_ERR_UNSUPPORTED;
   const size_t nrec = (size_t)p->batch * p->n_q_heads * pl.n_chunks;
   if (workspace_bytes < workspace_floats(p, pl) * sizeof(float)) return GH_ERR_WORKSPACE;
   const int64_t items = (int64_t)p->batch * p->n_kv_heads * pl.n_pass * pl.n_chunks;
@@ -248,7 +263,9 @@ int32_t gh_decode_attention(const gh_problem* p, const void* q, const void* k_ca
   block_params(p, &a.block_stride, &a.block_shift, &a.block_mask);
   a.n_q_heads = p->n_q_heads;
   a.n_kv_heads = p->n_kv_heads;
-  a.group = p->n_q_heads / p->n_kv_heads;
+  a.tokens = tokens_per_group(p);
+  a.real_group = p->n_q_heads / p->n_kv_heads;
+  a.group = a.real_group * a.tokens;
   a.n_slots = p->n_slots;
   a.row_limit = p->max_ctx_len < p->slot_capacity ? p->max_ctx_len : p->slot_capacity;
   a.chunk_rows = pl.chunk_rows;
@@ -256,7 +273,7 @@ int32_t gh_decode_attention(const gh_problem* p, const void* q, const void* k_ca
   a.heads_per_pass = pl.per_pass;
   a.n_pass = pl.n_pass;
   a.n_items = (int32_t)items;
-  a.batch = p->batch;
+  a.batch = p->batch / a.tokens;                 // groups
   a.n_workers = pl.n_workers;
   a.min_share = pl.min_share;
   a.scale_log2e = p->scale * 1.44269504088896340736f;
@@ -265,11 +282,18 @@ int32_t gh_decode_attention(const gh_problem* p, const void* q, const void* k_ca
   const bool bf16 = p->dtype == GH_BF16;
   if (pl.balanced) {
     const dim3 grid(pl.n_workers / 4), block(256);
-    const size_t lds = (size_t)(3 * p->batch + 1) * sizeof(uint32_t);
-    if (bf16)
-      hipLaunchKernelGGL(gh::attn_mfma_balanced_kernel<true>, grid, block, lds, s, a);
-    else
-      hipLaunchKernelGGL(gh::attn_mfma_balanced_kernel<false>, grid, block, lds, s, a);
+    const size_t lds = (size_t)(3 * a.batch + 1) * sizeof(uint32_t);
+    if (a.tokens > 1) {
+      if (bf16)
+        hipLaunchKernelGGL((gh::attn_mfma_balanced_kernel<true, true>), grid, block, lds, s, a);
+      else
+        hipLaunchKernelGGL((gh::attn_mfma_balanced_kernel<false, true>), grid, block, lds, s, a);
+    } else {
+      if (bf16)
+        hipLaunchKernelGGL((gh::attn_mfma_balanced_kernel<true, false>), grid, block, lds, s, a);
+      else
+        hipLaunchKernelGGL((gh::attn_mfma_balanced_kernel<false, false>), grid, block, lds, s, a);
+    }
   } else if (pl.kernel == GH_KERNEL_MFMA) {
     const dim3 grid(a.n_items), block(64);
     if (bf16)

@@ -74,6 +74,11 @@ def test_status_strings():
     (dict(chunk_rows=-64), G.GH_ERR_SHAPE),
     (dict(q_batch_stride=32 * 128 - 8), G.GH_ERR_SHAPE),
     (dict(new_batch_stride=-8), G.GH_ERR_SHAPE),
+    (dict(tokens_per_group=-1), G.GH_ERR_SHAPE),
+    (dict(tokens_per_group=3), G.GH_ERR_SHAPE),                       # batch 4 is no multiple of 3
+    (dict(tokens_per_group=2, kernel=G.GH_KERNEL_VALU), G.GH_ERR_UNSUPPORTED),
+    (dict(tokens_per_group=2, chunk_rows=64), G.GH_ERR_UNSUPPORTED),
+    (dict(tokens_per_group=65, batch=130), G.GH_ERR_UNSUPPORTED),
     (dict(block=(-32, 4096)), G.GH_ERR_SHAPE),
     (dict(block=(64, 0)), G.GH_ERR_SHAPE),
     (dict(block=(48, 8 * 48 * 128)), G.GH_ERR_UNSUPPORTED),

@@ -302,6 +302,88 @@ def test_mixed_prefill_and_decode_batch(kernel, chunk_rows):
     assert np.array_equal(W.bits(inp["v_cache"]), host["v_cache"])
 
 
+# ------------------------------------------------------------------ token groups
+def _grouped_rows(T):
+    """Token rows in groups of T: chunks of two prompts, decode entries, padding.  Each row is
+    (rows cached before it, slot, live); a padding row sits on a spare slot of its own."""
+    spare = iter(range(10, 1000))
+    rows = []
+
+    def group(live_rows, pad_first=False):
+        pad = [(0, next(spare), False) for _ in range(T - len(live_rows))]
+        rows.extend(pad + live_rows if pad_first else live_rows + pad)
+
+    def chunk(slot, cached, n_tokens):
+        toks = [(cached + t, slot, True) for t in range(n_tokens)]
+        for i in range(0, n_tokens, T):
+            group(toks[i:i + T])
+
+    chunk(2, 100, 2 * T + 2)                  # prompt A: a chunk over several groups, ragged end
+    group([(300, 0, True)])                   # decode entries: one live row per group
+    group([(31, 5, True)], pad_first=True)    # ... the live row need not come first
+    group([])                                 # nothing live at all
+    chunk(3, 0, T + 1)                        # prompt C starts from an empty slot
+    group([(700, 6, True)])
+    return rows
+
+
+@pytest.mark.parametrize("dtype", ["bf16", "f16"])
+@pytest.mark.parametrize("H,Hkv,T", [(8, 1, 2), (8, 2, 4), (4, 4, 16), (8, 2, 3), (16, 2, 4),
+                                     (6, 2, 5), (2, 2, 40)])
+def test_token_groups_share_the_slot_stream_and_match_the_oracle(H, Hkv, T, dtype):
+    """tokens_per_group = T: the T rows of a group are head columns of the same tiles, each masked
+    at its own length.  The result must be the per-row oracle's (causal inside a chunk, zero for
+    padding rows) and agree with the undeclared batch; appends are untouched."""
+    rows = _grouped_rows(T)
+    lengths = np.array([r[0] for r in rows], dtype=np.int32)
+    slots = np.array([r[1] for r in rows], dtype=np.int32)
+    live = np.array([r[2] for r in rows])
+    w = small("groups", len(rows), H, Hkv, dtype, 69)
+    inp = W.make_inputs(w, DEV, lengths=lengths, n_slots=int(slots.max()) + 1, capacity=704,
+                        slots=slots)
+    host = Hh.host_copy(inp)
+    ctx = np.where(live, lengths + 1, 0).astype(np.int32)            # padding rows attend nothing
+    inp["ctx_len"] = torch.from_numpy(ctx).to(DEV)
+    host["ctx_len"] = ctx
+    want = Hh.oracle_step(inp, host)
+    assert not want[~live].any()
+
+    outs = {}
+    for tpg in (T, 0):
+        p = G.problem_from_inputs(inp, tokens_per_group=tpg)
+        ws = G.alloc_workspace(p, DEV)
+        ws.fill_(float("nan"))
+        out = torch.full((w.batch, H, 128), float("nan"), dtype=torch.float32, device=DEV)
+        G.decode_step(p, inp, ws, out, append=(tpg == T))
+        torch.cuda.synchronize()
+        outs[tpg] = out.cpu().numpy()
+        Hh.assert_parity(outs[tpg], want, f"tokens_per_group={tpg}")
+    assert not outs[T][~live].any()
+    assert np.abs(outs[T] - outs[0]).max() < 2e-5
+    assert np.array_equal(W.bits(inp["k_cache"]), host["k_cache"])
+    assert np.array_equal(W.bits(inp["v_cache"]), host["v_cache"])
+
+
+def test_token_group_row_on_another_slot_gets_no_rows():
+    """A live row whose slot differs from that of the group's first live row is outside the
+    declaration: it gets zeros, the rest of the group is unaffected."""
+    lengths = np.array([50, 51, 40, 52], dtype=np.int32)
+    slots = np.array([1, 1, 2, 1], dtype=np.int32)                   # row 2 breaks the group
+    w = small("stray", 4, 8, 2, "bf16", 70)
+    inp = W.make_inputs(w, DEV, lengths=lengths, n_slots=3, capacity=64, slots=slots)
+    host = Hh.host_copy(inp)
+    want = Hh.oracle_step(inp, host)
+    p = G.problem_from_inputs(inp, tokens_per_group=4)
+    ws = G.alloc_workspace(p, DEV)
+    ws.fill_(float("nan"))
+    out = torch.full((4, 8, 128), float("nan"), dtype=torch.float32, device=DEV)
+    G.decode_step(p, inp, ws, out)
+    torch.cuda.synchronize()
+    got = out.cpu().numpy()
+    assert not got[2].any()
+    Hh.assert_parity(got[[0, 1, 3]], want[[0, 1, 3]], "rest of the group")
+
+
 # ------------------------------------------------------------------ the merge on its own
 def test_reduce_matches_oracle_merge_of_oracle_partials():
     w = small("red", 3, 4, 2, "bf16", 65)
