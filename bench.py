@@ -95,6 +95,8 @@ def main():
     ap.add_argument("--group", type=int, default=0, metavar="T",
                     help="experiment: declare tokens_per_group = T (rows kT..kT+T-1 share a slot); "
                          "the GB/s printed then counts every row's K/V as if read separately")
+    ap.add_argument("--out16", action="store_true",
+                    help="experiment: the merge stores the model's 16-bit type (gh_decode_reduce_native)")
     ap.add_argument("--paged", action="store_true",
                     help="keep the caches in a gh_slot_pool (virtual slots, pages mapped on demand)")
     ap.add_argument("--page-rows", type=int, default=1024)
@@ -183,7 +185,9 @@ def main():
     p = G.problem_from_inputs(inp, chunk_rows=args.chunk_rows, kernel=kernel,
                               tokens_per_group=args.group)
     ws = G.alloc_workspace(p)
-    out = torch.empty((w.batch, w.n_q_heads, w.head_dim), dtype=torch.float32, device="cuda")
+    out = torch.empty((w.batch, w.n_q_heads, w.head_dim), device="cuda",
+                      dtype=W.TORCH_DTYPE[w.dtype] if args.out16 else torch.float32)
+    reduce = G.gh_decode_reduce_native if args.out16 else G.gh_decode_reduce
     ctx = inp["lengths"].astype(np.int64) + 1
     step_bytes = W.algorithmic_bytes(w, ctx)
     attn_bytes = W.attention_bytes(w, ctx)
@@ -203,7 +207,7 @@ def main():
                                       inp["ctx_len"], ws))
         if events is not None:
             events[1].record()
-        G.check(G.gh_decode_reduce(p, ws, inp["ctx_len"], out))
+        G.check(reduce(p, ws, inp["ctx_len"], out))
         if events is not None:
             events[2].record()
 
@@ -264,7 +268,8 @@ def main():
                                f"H_kv={w.n_kv_heads}, d={w.head_dim}, lengths={list(w.lengths)}, "
                                f"seed={w.seed}",
                    "kernel": args.kernel, "chunk_rows": chunk_rows, "n_chunks": n_chunks,
-                   "step": "gh_kv_append + gh_decode_attention + gh_decode_reduce",
+                   "step": "gh_kv_append + gh_decode_attention + "
+                           + ("gh_decode_reduce_native" if args.out16 else "gh_decode_reduce"),
                    "paged_slots": paged_info, "hip_graph_ms_per_step": graph_ms,
                    "step_algorithmic_bytes": step_bytes,
                    "step_GBps": step_bytes / (elapsed / args.steps) / 1e9},
@@ -274,7 +279,7 @@ def main():
                      "traffic": args.traffic_bytes if args.traffic_bytes is not None else (
                          MEASURED_TRAFFIC_BYTES.get(w.name)
                          if args.kernel == "auto" and not (args.chunk_rows or args.batch or args.const_len or args.capacity or args.paged
-                                                      or args.mixed or args.prefill or args.group)
+                                                      or args.mixed or args.prefill or args.group or args.out16)
                          else None),
                      "algorithmic_bytes_per_launch": attn_bytes,
                      "avg_launch_ms": float(attn_ms.mean())},
