@@ -167,3 +167,34 @@ def search(model, tier1, tier2, link, tier2_context_bytes, max_tier1_nodes, max_
 def measured_tier2_profile(name="tier2_mi355x_llama2_70b.json"):
     """The Tier-2 curve measured on an MI355X with this library (written by profile_tier2.py)."""
     return Profile.load(os.path.join(HERE, "data", name))
+
+
+def main():
+    """Worked example: Llama2-70B, Tier 1 from the roofline stand-in, Tier 2 from the measured
+    MI355X curve.  `python -m paper_2501_11779_amd.config_search`"""
+    import argparse
+    import time
+    ap = argparse.ArgumentParser()
+    ap.add_argument("--tier1-bandwidth", type=float, default=6.4e12, help="bytes/s (default 80%% of 8 TB/s)")
+    ap.add_argument("--tier1-flops", type=float, default=1.5e15, help="flop/s reached by the Tier-1 GEMMs")
+    ap.add_argument("--link-bandwidth", type=float, default=50e9, help="bytes/s between the tiers")
+    ap.add_argument("--link-rtt", type=float, default=20e-6, help="seconds")
+    ap.add_argument("--tier2-context-gib", type=float, default=200.0, help="context memory per Tier-2 device")
+    ap.add_argument("--max-tier1", type=int, default=8)
+    ap.add_argument("--max-tier2-per-tier1", type=int, default=4)
+    ap.add_argument("--top", type=int, default=5)
+    args = ap.parse_args()
+    tier2 = measured_tier2_profile()
+    tier1 = tier1_roofline_profile(LLAMA2_70B, args.tier1_bandwidth, args.tier1_flops)
+    link = Link(rtt=args.link_rtt, bandwidth=args.link_bandwidth)
+    t0 = time.perf_counter()
+    cands = search(LLAMA2_70B, tier1, tier2, link, args.tier2_context_gib * 2 ** 30, args.max_tier1,
+                   args.max_tier2_per_tier1)
+    print(f"{len(cands)} configurations simulated in {time.perf_counter() - t0:.1f} s")
+    for c in cands[:args.top]:
+        print(f"K={c.K} K'={c.K_prime} B={c.B} in-flight={c.in_flight} TBT={c.tbt * 1e3:.1f} ms "
+              f"{c.tokens_per_s:.3e} tokens/s")
+
+
+if __name__ == "__main__":
+    main()
