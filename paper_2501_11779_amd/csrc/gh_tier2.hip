@@ -241,6 +241,9 @@ int32_t gh_decode_attention(const gh_problem* p, const void* q, const void* k_ca
     return GH_ERR_UNSUPPORTED;
   const Plan pl = make_plan(p);
   if (tokens_per_group(p) > 1 && !pl.balanced) return GH_ERR_UNSUPPORTED;
+  // the records of one (group, kv head) are addressed with 32-bit byte offsets from its first
+  if ((int64_t)tokens_per_group(p) * p->n_q_heads * pl.n_chunks * gh::kHeadDim * 4 > 0x7fffffff)
+    return GH_ERR_UNSUPPORTED;
   const size_t nrec = (size_t)p->batch * p->n_q_heads * pl.n_chunks;
   if (workspace_bytes < workspace_floats(p, pl) * sizeof(float)) return GH_ERR_WORKSPACE;
   const int64_t items = (int64_t)p->batch * p->n_kv_heads * pl.n_pass * pl.n_chunks;
