@@ -33,12 +33,12 @@ void block_params(const gh_problem* p, int64_t* stride, int32_t* shift, int32_t*
 
 bool aligned16(const void* p) { return (reinterpret_cast<uintptr_t>(p) & 15u) == 0; }
 
-// Everything about gh_problem that can be judged on the host.
 constexpr int kBalancedMaxBatch = 4096;     // three per-group arrays live in LDS (48 KB)
 constexpr int kMaxTokensPerGroup = 64;
 
 int tokens_per_group(const gh_problem* p) { return p->tokens_per_group > 1 ? p->tokens_per_group : 1; }
 
+// Everything about gh_problem that can be judged on the host.
 int32_t check_problem(const gh_problem* p) {
   if (!p) return GH_ERR_NULL;
   if (p->batch < 0 || p->n_q_heads <= 0 || p->n_kv_heads <= 0 || p->n_slots <= 0 ||
