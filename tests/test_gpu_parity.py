@@ -364,6 +364,33 @@ def test_token_groups_share_the_slot_stream_and_match_the_oracle(H, Hkv, T, dtyp
     assert np.array_equal(W.bits(inp["v_cache"]), host["v_cache"])
 
 
+@pytest.mark.parametrize("layout", ["token_major", "head_blocked"])
+def test_token_groups_on_other_cache_layouts(layout):
+    """Grouping and addressing are independent: the same grouped batch on a token-major and on a
+    head-blocked cache (blocks of 32 rows, so every chunk crosses block borders)."""
+    T = 4
+    rows = _grouped_rows(T)
+    lengths = np.array([r[0] for r in rows], dtype=np.int32)
+    slots = np.array([r[1] for r in rows], dtype=np.int32)
+    live = np.array([r[2] for r in rows])
+    w = small("groups2", len(rows), 8, 2, "bf16", 71)
+    inp = W.make_inputs(w, DEV, lengths=lengths, n_slots=int(slots.max()) + 1, capacity=704,
+                        slots=slots, layout=layout, block_rows=32)
+    host = Hh.host_copy(inp)
+    ctx = np.where(live, lengths + 1, 0).astype(np.int32)
+    inp["ctx_len"] = torch.from_numpy(ctx).to(DEV)
+    host["ctx_len"] = ctx
+    want = Hh.oracle_step(inp, host)
+    p = G.problem_from_inputs(inp, tokens_per_group=T)
+    ws = G.alloc_workspace(p, DEV)
+    ws.fill_(float("nan"))
+    out = torch.full((w.batch, 8, 128), float("nan"), dtype=torch.float32, device=DEV)
+    G.decode_step(p, inp, ws, out)
+    torch.cuda.synchronize()
+    Hh.assert_parity(out.cpu().numpy(), want, f"groups on {layout}")
+    assert np.array_equal(W.bits(inp["k_cache"]), host["k_cache"])
+
+
 def test_token_group_row_on_another_slot_gets_no_rows():
     """A live row whose slot differs from that of the group's first live row is outside the
     declaration: it gets zeros, the rest of the group is unaffected."""
