@@ -43,6 +43,9 @@ __global__ __launch_bounds__(256) void decode_reduce_kernel(const ReduceArgs a) 
   const float2 o1 = two ? *reinterpret_cast<const float2*>(o + kHeadDim) : make_float2(0.f, 0.f);
   const float m0 = m[0], l0 = l[0];
   const float m1 = two ? m[1] : kNegInf, l1 = two ? l[1] : 0.f;
+  // ... and so are the headers of the first 64 records, one per lane, for heads with more
+  const int ch = lane < a.n_chunks ? lane : 0;
+  const float mh = m[ch], lh = l[ch];
   int used = a.ws_n[row];
   used = used < 0 ? 0 : used < a.n_chunks ? used : a.n_chunks;
 
@@ -72,8 +75,8 @@ __global__ __launch_bounds__(256) void decode_reduce_kernel(const ReduceArgs a) 
     float M = kNegInf;
     for (int c0 = 0; c0 < used; c0 += 64) {
       const int c = c0 + lane;
-      const float lc = c < used ? l[c] : 0.f;
-      const float mc = c < used ? m[c] : kNegInf;
+      const float lc = c >= used ? 0.f : c0 == 0 ? lh : l[c];
+      const float mc = c >= used ? kNegInf : c0 == 0 ? mh : m[c];
       M = fmaxf(M, lc > 0.f ? mc : kNegInf);     // a record without rows carries no maximum
     }
     M = wave_max(M);
@@ -81,8 +84,8 @@ __global__ __launch_bounds__(256) void decode_reduce_kernel(const ReduceArgs a) 
     if (M != kNegInf) {
       for (int c0 = 0; c0 < used; c0 += 64) {
         const int c = c0 + lane;
-        const float lc = c < used ? l[c] : 0.f;
-        const float mc = c < used ? m[c] : kNegInf;
+        const float lc = c >= used ? 0.f : c0 == 0 ? lh : l[c];
+        const float mc = c >= used ? kNegInf : c0 == 0 ? mh : m[c];
         const float w = lc > 0.f ? fast_exp2(mc - M) : 0.f;   // this lane's record weight
         const float wl = w * lc;
         const int n = used - c0 < 64 ? used - c0 : 64;
