@@ -49,9 +49,10 @@
  *     lets the tokens of a prefill chunk share one pass over their slot.  Batch
  *     rows kT .. kT+T-1 form group k and address one slot; each row keeps its
  *     own ctx_len (and q, position, output row).  gh_decode_attention then
- *     streams the slot's K/V rows once per group and kv head -- the T*G query
- *     heads of a group fill the 16 head columns of a matrix-core tile, each
- *     column masked at its own token's length -- instead of once per row.  A
+ *     streams the slot's K/V rows once per 32 of the T*G query heads a group
+ *     has per kv head -- they fill the head columns of two matrix-core tiles
+ *     fed from one stream, each column masked at its own token's length --
+ *     instead of once per row.  A
  *     row with ctx_len 0, a bad slot id, or a slot other than that of the
  *     group's first live row gets no rows (output zero), so short groups are
  *     padded with ctx_len = 0 rows and a decode entry is a group with one live

@@ -407,8 +407,12 @@ struct TileCursor {
   int slot;         // cache slot (0 when n == 0)
 };
 
-template <bool BF16, bool GROUPED>
-__global__ __launch_bounds__(256, 2) void attn_mfma_balanced_kernel(const AttnArgs a) {
+//
+// P = passes of 16 head columns a wave carries through a strip at once (own Q operand, running
+// state and accumulators per pass, one stream of tiles for all): 1 for decode, 2 for token groups
+// with more than 16 head columns, at one wave per SIMD instead of two.
+template <bool BF16, bool GROUPED, int P>
+__global__ __launch_bounds__(256, P == 1 ? 2 : 1) void attn_mfma_balanced_kernel(const AttnArgs a) {
   extern __shared__ uint32_t lds[];
   __shared__ uint32_t part[256];
   const int tid = threadIdx.x;
@@ -482,11 +486,16 @@ __global__ __launch_bounds__(256, 2) void attn_mfma_balanced_kernel(const AttnAr
       }
     }
   };
-  auto pass_of = [&](uint32_t sib, int& g, int& pass, int& nh) {
+  // Strip `sib` of a group: kv head g, passes pass0 .. pass0 + P - 1 of which nh[i] columns are
+  // real (0 for a pass beyond the group's columns; the first pass of a strip always has some).
+  auto pass_of = [&](uint32_t sib, int& g, int& pass0, int (&nh)[P]) {
     g = (int)(sib / (uint32_t)a.n_pass);
-    pass = (int)(sib % (uint32_t)a.n_pass);
-    const int left = a.group - pass * a.heads_per_pass;
-    nh = left < a.heads_per_pass ? left : a.heads_per_pass;
+    pass0 = (int)(sib % (uint32_t)a.n_pass) * P;
+#pragma unroll
+    for (int i = 0; i < P; ++i) {
+      const int left = a.group - (pass0 + i) * a.heads_per_pass;
+      nh[i] = left < 0 ? 0 : left < a.heads_per_pass ? left : a.heads_per_pass;
+    }
   };
   // Rows the lane's head column attends.  GROUPED (T > 1): the token row's own length if it is live
   // and on the group's slot, loaded with the Q operand, unconditionally, and taken into use with
@@ -552,62 +561,101 @@ __global__ __launch_bounds__(256, 2) void attn_mfma_balanced_kernel(const AttnAr
 
   // qop, lim: operand and row limit of the strip being computed; qnext, lnext: raw rows and limit
   // of the following strip, in flight for a whole strip before they are taken into use; qnext_nh:
-  // how many of its columns are real; lnext_slot: its group's slot.
-  u32x4 qop[4], qnext[4];
-  int g, pass, nh, qnext_nh = 0, lnext_slot = 0;
-  pass_of(cp.sib, g, pass, nh);
-  load_q(qnext, a, cp.b, g, pass, nh, hn, c);
-  Limit lnext = load_limit(cp, cp.b, g, pass, nh);
-  keep_real_heads(qop, qnext, nh, hn);
-  int lim = rows_of(lnext, cp.slot);
+  // how many of its columns are real; lnext_slot: its group's slot.  One of each per pass.
+  u32x4 qop[P][4], qnext[P][4];
+  Limit lnext[P];
+  int lim[P], nh[P], qnext_nh[P];
+  int g, pass0;                       // kv head and first pass of the strip being computed
+  int qg = 0, qpass0 = 0, lnext_slot = 0;   // ... and of the strip whose rows are in flight
+  // Q rows and limits of the P passes of a strip; a pass without columns fetches the first's
+  auto fetch = [&](const TileCursor& cu, int b, int fg, int fpass0, const int (&fnh)[P]) {
+#pragma unroll
+    for (int i = 0; i < P; ++i) {
+      const int pass = fnh[i] > 0 ? fpass0 + i : fpass0;
+      load_q(qnext[i], a, b, fg, pass, fnh[i], hn, c);
+      lnext[i] = load_limit(cu, b, fg, pass, fnh[i]);
+    }
+  };
+  auto take = [&](const int (&tnh)[P], int slot) {
+#pragma unroll
+    for (int i = 0; i < P; ++i) {
+      keep_real_heads(qop[i], qnext[i], tnh[i], hn);
+      lim[i] = rows_of(lnext[i], slot);
+    }
+  };
+  pass_of(cp.sib, g, pass0, nh);
+  fetch(cp, cp.b, g, pass0, nh);
+  take(nh, cp.slot);
   next_strip(qs);
+#pragma unroll
+  for (int i = 0; i < P; ++i) qnext_nh[i] = 0;
   if (qs.t < t_end) {
-    int qg, qpass;
-    pass_of(qs.sib, qg, qpass, qnext_nh);
-    load_q(qnext, a, qs.b, qg, qpass, qnext_nh, hn, c);
-    lnext = load_limit(qs, qs.b, qg, qpass, qnext_nh);
+    pass_of(qs.sib, qg, qpass0, qnext_nh);
+    fetch(qs, qs.b, qg, qpass0, qnext_nh);
     lnext_slot = qs.slot;
   }
 
-  f32x4 acc[8];
+  f32x4 acc[P][8];
+  float m[P], l[P];
 #pragma unroll
-  for (int tcol = 0; tcol < 8; ++tcol) acc[tcol] = f32x4{0.f, 0.f, 0.f, 0.f};
-  float m = kNegInf, l = 0.f;
+  for (int i = 0; i < P; ++i) {
+#pragma unroll
+    for (int tcol = 0; tcol < 8; ++tcol) acc[i][tcol] = f32x4{0.f, 0.f, 0.f, 0.f};
+    m[i] = kNegInf;
+    l[i] = 0.f;
+  }
 
   // One tile of arithmetic; closes the record when the tile ends this wave's piece of the strip.
   auto compute = [&](const TileRegs& regs) {
-    if (cp.n > 0)
-      process_tile<BF16>(regs, qop, acc, m, l, a.scale_log2e, (int)cp.lt * 32, lim, c);
+    if (cp.n > 0) {
+#pragma unroll
+      for (int i = 0; i < P; ++i)
+        if (nh[i] > 0)
+          process_tile<BF16>(regs, qop[i], acc[i], m[i], l[i], a.scale_log2e, (int)cp.lt * 32,
+                             lim[i], c);
+    }
     const bool strip_end = cp.lt + 1 == cp.tiles;
     if (strip_end || cp.t + 1 == t_end) {
       const uint32_t strip_t0 = cp.t - cp.lt;                  // global index of the strip's tile 0
       int rec = (int)(gw - strip_t0 / share);
-      pass_of(cp.sib, g, pass, nh);
       if (cp.n > 0) {
-        store_record(a, cp.b, g, pass, nh, rec, acc, m, l, hn, c);
+#pragma unroll
+        for (int i = 0; i < P; ++i)
+          if (nh[i] > 0) store_record(a, cp.b, g, pass0 + i, nh[i], rec, acc[i], m[i], l[i], hn, c);
         ++rec;
       }
-      if (strip_end && hn < nh && c == 0)                     // records in use for these heads
-        a.ws_n[column_index(a, cp.b, g, pass, hn)] = rec;
+      if (strip_end && c == 0) {                               // records in use for these heads
+#pragma unroll
+        for (int i = 0; i < P; ++i)
+          if (hn < nh[i]) a.ws_n[column_index(a, cp.b, g, pass0 + i, hn)] = rec;
+      }
       if (cp.t + 1 < t_end) {                                  // the next tile opens a strip
 #pragma unroll
-        for (int tcol = 0; tcol < 8; ++tcol) acc[tcol] = f32x4{0.f, 0.f, 0.f, 0.f};
-        m = kNegInf;
-        l = 0.f;
-        keep_real_heads(qop, qnext, qnext_nh, hn);
-        lim = rows_of(lnext, lnext_slot);
+        for (int i = 0; i < P; ++i) {
+#pragma unroll
+          for (int tcol = 0; tcol < 8; ++tcol) acc[i][tcol] = f32x4{0.f, 0.f, 0.f, 0.f};
+          m[i] = kNegInf;
+          l[i] = 0.f;
+        }
+        take(qnext_nh, lnext_slot);
+        g = qg;
+        pass0 = qpass0;
+#pragma unroll
+        for (int i = 0; i < P; ++i) nh[i] = qnext_nh[i];
         next_strip(qs);
         {
           // unconditional: when no strip follows, this strip's rows are fetched again (unused)
           const bool more = qs.t < t_end;
           const int qb = more ? qs.b : cp.b;
-          int qg, qpass;
-          pass_of(more ? qs.sib : cp.sib, qg, qpass, qnext_nh);
-          load_q(qnext, a, qb, qg, qpass, qnext_nh, hn, c);
+          pass_of(more ? qs.sib : cp.sib, qg, qpass0, qnext_nh);
           if constexpr (GROUPED) {
-            lnext = load_limit(qs, qb, qg, qpass, qnext_nh);
+            fetch(qs, qb, qg, qpass0, qnext_nh);
           } else {
-            lnext = Limit{0, more ? qs.n : cp.n};
+#pragma unroll
+            for (int i = 0; i < P; ++i) {
+              load_q(qnext[i], a, qb, qg, qpass0 + i, qnext_nh[i], hn, c);
+              lnext[i] = Limit{0, more ? qs.n : cp.n};
+            }
           }
           lnext_slot = more ? qs.slot : cp.slot;
         }

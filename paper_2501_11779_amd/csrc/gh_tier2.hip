@@ -114,6 +114,8 @@ struct Plan {
   int kernel, chunk_rows, n_chunks, per_pass, n_pass;
   bool balanced;            // equal shares of 32-row tiles per wave instead of fixed chunks
   int n_workers, min_share; // balanced split only
+  int passes_per_strip;     // balanced split: passes a wave carries through a strip at once;
+                            // n_pass then counts strips per (group, kv head)
 };
 
 constexpr int kBalancedWavesPerCU = 8;      // resident waves of the MFMA kernel per compute unit
@@ -125,15 +127,22 @@ Plan make_plan(const gh_problem* p) {
   head_passes(p, pl.kernel, &pl.per_pass, &pl.n_pass);
   pl.balanced = false;
   pl.n_workers = pl.min_share = 0;
+  pl.passes_per_strip = 1;
   const int groups = p->batch / tokens_per_group(p);
-  const int64_t strips = (int64_t)(groups > 0 ? groups : 1) * p->n_kv_heads * pl.n_pass;
+  // Token groups with more than 16 head columns: two passes share one stream of tiles, at one
+  // wave per SIMD (the second pass's operands and accumulators take the other wave's registers).
+  const int pps = tokens_per_group(p) > 1 && pl.n_pass > 1 ? 2 : 1;
+  const int n_strip = (pl.n_pass + pps - 1) / pps;
+  const int64_t strips = (int64_t)(groups > 0 ? groups : 1) * p->n_kv_heads * n_strip;
   const int64_t max_tiles = p->max_ctx_len > 0 ? (p->max_ctx_len + 31) / 32 : 1;
   if (pl.kernel == GH_KERNEL_MFMA && p->chunk_rows == 0 && groups <= kBalancedMaxBatch &&
       strips * max_tiles < 0x7fffffff) {
     // Records per head: enough for the longest strip when strips are up to four times the
     // average length; beyond that the share per wave grows instead (min_share).
     pl.balanced = true;
-    pl.n_workers = kComputeUnits * kBalancedWavesPerCU;
+    pl.passes_per_strip = pps;
+    pl.n_pass = n_strip;
+    pl.n_workers = kComputeUnits * (pps == 1 ? kBalancedWavesPerCU : kBalancedWavesPerCU / 2);
     int64_t c = (4 * (int64_t)pl.n_workers + strips - 1) / strips + 1;
     if (c < 2) c = 2;
     if (c > kBalancedMaxRecords) c = kBalancedMaxRecords;
@@ -286,16 +295,21 @@ int32_t gh_decode_attention(const gh_problem* p, const void* q, const void* k_ca
   if (pl.balanced) {
     const dim3 grid(pl.n_workers / 4), block(256);
     const size_t lds = (size_t)(3 * a.batch + 1) * sizeof(uint32_t);
-    if (a.tokens > 1) {
+    if (pl.passes_per_strip == 2) {
       if (bf16)
-        hipLaunchKernelGGL((gh::attn_mfma_balanced_kernel<true, true>), grid, block, lds, s, a);
+        hipLaunchKernelGGL((gh::attn_mfma_balanced_kernel<true, true, 2>), grid, block, lds, s, a);
       else
-        hipLaunchKernelGGL((gh::attn_mfma_balanced_kernel<false, true>), grid, block, lds, s, a);
+        hipLaunchKernelGGL((gh::attn_mfma_balanced_kernel<false, true, 2>), grid, block, lds, s, a);
+    } else if (a.tokens > 1) {
+      if (bf16)
+        hipLaunchKernelGGL((gh::attn_mfma_balanced_kernel<true, true, 1>), grid, block, lds, s, a);
+      else
+        hipLaunchKernelGGL((gh::attn_mfma_balanced_kernel<false, true, 1>), grid, block, lds, s, a);
     } else {
       if (bf16)
-        hipLaunchKernelGGL((gh::attn_mfma_balanced_kernel<true, false>), grid, block, lds, s, a);
+        hipLaunchKernelGGL((gh::attn_mfma_balanced_kernel<true, false, 1>), grid, block, lds, s, a);
       else
-        hipLaunchKernelGGL((gh::attn_mfma_balanced_kernel<false, false>), grid, block, lds, s, a);
+        hipLaunchKernelGGL((gh::attn_mfma_balanced_kernel<false, false, 1>), grid, block, lds, s, a);
     }
   } else if (pl.kernel == GH_KERNEL_MFMA) {
     const dim3 grid(a.n_items), block(64);
