@@ -87,7 +87,7 @@ typedef enum { GH_F16 = 0, GH_BF16 = 1 } gh_dtype;
 typedef enum {
   GH_KERNEL_AUTO = 0, /* the library's measured choice (currently always MFMA)   */
   GH_KERNEL_VALU = 1, /* fp32 vector arithmetic, passes of up to 8 heads          */
-  GH_KERNEL_MFMA = 2  /* matrix-core tiles, passes of up to 16 heads              */
+  GH_KERNEL_MFMA = 2  /* matrix-core tiles, passes of up to 16 heads, two at once  */
 } gh_kernel;
 
 /* Bits OR-ed into *dev_status by gh_kv_append. */

@@ -129,9 +129,10 @@ Plan make_plan(const gh_problem* p) {
   pl.n_workers = pl.min_share = 0;
   pl.passes_per_strip = 1;
   const int groups = p->batch / tokens_per_group(p);
-  // Token groups with more than 16 head columns: two passes share one stream of tiles, at one
-  // wave per SIMD (the second pass's operands and accumulators take the other wave's registers).
-  const int pps = tokens_per_group(p) > 1 && pl.n_pass > 1 ? 2 : 1;
+  // More than 16 head columns per kv head (a token group, or a head group above 16): two passes
+  // share one stream of tiles, at one wave per SIMD (the second pass's operands and accumulators
+  // take the other wave's registers).
+  const int pps = pl.n_pass > 1 ? 2 : 1;
   const int n_strip = (pl.n_pass + pps - 1) / pps;
   const int64_t strips = (int64_t)(groups > 0 ? groups : 1) * p->n_kv_heads * n_strip;
   const int64_t max_tiles = p->max_ctx_len > 0 ? (p->max_ctx_len + 31) / 32 : 1;
@@ -295,11 +296,16 @@ int32_t gh_decode_attention(const gh_problem* p, const void* q, const void* k_ca
   if (pl.balanced) {
     const dim3 grid(pl.n_workers / 4), block(256);
     const size_t lds = (size_t)(3 * a.batch + 1) * sizeof(uint32_t);
-    if (pl.passes_per_strip == 2) {
+    if (pl.passes_per_strip == 2 && a.tokens > 1) {
       if (bf16)
         hipLaunchKernelGGL((gh::attn_mfma_balanced_kernel<true, true, 2>), grid, block, lds, s, a);
       else
         hipLaunchKernelGGL((gh::attn_mfma_balanced_kernel<false, true, 2>), grid, block, lds, s, a);
+    } else if (pl.passes_per_strip == 2) {
+      if (bf16)
+        hipLaunchKernelGGL((gh::attn_mfma_balanced_kernel<true, false, 2>), grid, block, lds, s, a);
+      else
+        hipLaunchKernelGGL((gh::attn_mfma_balanced_kernel<false, false, 2>), grid, block, lds, s, a);
     } else if (a.tokens > 1) {
       if (bf16)
         hipLaunchKernelGGL((gh::attn_mfma_balanced_kernel<true, true, 1>), grid, block, lds, s, a);
