@@ -26,7 +26,7 @@ HBM_PEAK_GBS = 8000.0   # MI355X published HBM3E peak
 # HBM bytes per gh_decode_attention launch (FETCH_SIZE + WRITE_SIZE, each scaled by what the same
 # counter reads for a plain 1 GiB device copy) from the rocprofv3 --pmc runs summarised in
 # profiles/gh_decode_attention_<workload>.md; valid for the library's default kernel and split.
-MEASURED_TRAFFIC_BYTES = {"c2": 1330004115, "c3": 2714996308, "c4": 9248024989, "c5": 2250367637}
+MEASURED_TRAFFIC_BYTES = {"c2": 1330104531, "c3": 2714920191, "c4": 9248076659, "c5": 2250269880}
 
 CONFIG_OF = {"c1": "configs[0]", "c2": "configs[1]", "c3": "configs[2]", "c4": "configs[3]",
              "c5": "configs[4]"}
