@@ -159,6 +159,27 @@ int32_t gh_decode_num_chunks(const gh_problem* p);
 size_t gh_decode_workspace_bytes(const gh_problem* p);
 
 /*
+ * The numbers behind the balanced split, for callers and tests that want to
+ * reason about it (host function).  Every strip -- (group, kv head, set of
+ * passes_per_strip passes of 16 head columns) -- counts ceil(rows / 32) tiles of
+ * 32 rows, at least one; the strips are laid end to end in batch order, kv head
+ * next, pass set fastest; wave w of n_workers takes tiles [w*share, (w+1)*share)
+ * with share = max(ceil(total / n_workers), min_share); the record a wave
+ * writes for a strip has index w - floor(first tile of the strip / share).
+ * min_share is what keeps that index below gh_decode_num_chunks for every
+ * batch whose lengths respect max_ctx_len.
+ */
+typedef struct {
+  int32_t balanced;           /* 0: fixed split, the other fields are 0          */
+  int32_t n_workers;          /* waves                                           */
+  int32_t min_share;          /* least tiles per wave                            */
+  int32_t passes_per_strip;   /* 1 or 2                                          */
+  int32_t strips_per_kv_head; /* pass sets per (group, kv head)                  */
+  int32_t n_chunks;           /* = gh_decode_num_chunks                          */
+} gh_split_plan;
+int32_t gh_decode_split_plan(const gh_problem* p, gh_split_plan* out);
+
+/*
  * Append (the C_k update of F2).  For each sequence b and kv head g, copies
  * the head_dim elements k_new[b][g][:] / v_new[b][g][:] ([B, H_kv, d],
  * contiguous) to row pos[b] of slot slot_id[b] of k_cache / v_cache.  A bit

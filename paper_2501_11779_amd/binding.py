@@ -22,7 +22,7 @@ GH_DEV_BAD_SLOT, GH_DEV_BAD_POS = 1, 2
 
 EXPORTS = ("gh_status_string", "gh_decode_chunk_rows", "gh_decode_num_chunks",
            "gh_decode_workspace_bytes", "gh_kv_append", "gh_decode_attention", "gh_decode_reduce",
-           "gh_decode_reduce_native")
+           "gh_decode_reduce_native", "gh_decode_split_plan")
 POOL_EXPORTS = ("gh_slot_pool_create", "gh_slot_pool_destroy", "gh_slot_pool_k", "gh_slot_pool_v",
                 "gh_slot_pool_strides", "gh_slot_pool_reserve", "gh_slot_pool_release",
                 "gh_slot_pool_mapped_rows", "gh_slot_pool_get_stats", "gh_slot_pool_blocks")
@@ -40,6 +40,12 @@ class gh_problem(C.Structure):
         ("q_batch_stride", C.c_int64), ("new_batch_stride", C.c_int64),
         ("block_rows", C.c_int32), ("tokens_per_group", C.c_int32), ("block_stride", C.c_int64),
     ]
+
+
+class gh_split_plan(C.Structure):
+    _fields_ = [("balanced", C.c_int32), ("n_workers", C.c_int32), ("min_share", C.c_int32),
+                ("passes_per_strip", C.c_int32), ("strips_per_kv_head", C.c_int32),
+                ("n_chunks", C.c_int32)]
 
 
 class gh_slot_pool_config(C.Structure):
@@ -83,6 +89,8 @@ def lib():
         L.gh_decode_chunk_rows.argtypes = [P]
         L.gh_decode_num_chunks.restype = C.c_int32
         L.gh_decode_num_chunks.argtypes = [P]
+        L.gh_decode_split_plan.restype = C.c_int32
+        L.gh_decode_split_plan.argtypes = [P, C.POINTER(gh_split_plan)]
         L.gh_decode_workspace_bytes.restype = C.c_size_t
         L.gh_decode_workspace_bytes.argtypes = [P]
         L.gh_kv_append.restype = C.c_int32
@@ -182,6 +190,12 @@ def gh_decode_reduce(p, workspace, ctx_len, out, stream=None):
 def gh_decode_reduce_native(p, workspace, ctx_len, out16, stream=None):
     return lib().gh_decode_reduce_native(C.byref(p), _ptr(workspace), _ptr(ctx_len), _ptr(out16),
                                          _stream(stream))
+
+
+def gh_decode_split_plan(p):
+    out = gh_split_plan()
+    check(lib().gh_decode_split_plan(C.byref(p), C.byref(out)))
+    return out
 
 
 def check(status):

@@ -202,6 +202,23 @@ int32_t gh_decode_num_chunks(const gh_problem* p) {
   return make_plan(p).n_chunks;
 }
 
+int32_t gh_decode_split_plan(const gh_problem* p, gh_split_plan* out) {
+  const int32_t st = check_problem(p);
+  if (st != GH_OK) return st;
+  if (!out) return GH_ERR_NULL;
+  const Plan pl = make_plan(p);
+  *out = gh_split_plan{};
+  out->n_chunks = pl.n_chunks;
+  if (pl.balanced) {
+    out->balanced = 1;
+    out->n_workers = pl.n_workers;
+    out->min_share = pl.min_share;
+    out->passes_per_strip = pl.passes_per_strip;
+    out->strips_per_kv_head = pl.n_pass;
+  }
+  return GH_OK;
+}
+
 size_t gh_decode_workspace_bytes(const gh_problem* p) {
   if (check_problem(p) != GH_OK) return 0;
   return workspace_floats(p, make_plan(p)) * sizeof(float);

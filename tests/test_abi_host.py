@@ -164,3 +164,87 @@ def test_problem_struct_matches_header_field_order():
         fields += [(n.strip(), ctype) for n in names.split(",")]
     want = {"int32_t": C.c_int32, "int64_t": C.c_int64, "float": C.c_float}
     assert [(n, want[t]) for n, t in fields] == list(G.gh_problem._fields_)
+
+
+# ------------------------------------------------------------------ the balanced split, emulated
+def _emulate_balanced_split(plan, group_rows, n_kv_heads):
+    """The split as include/gh_tier2.h words it, in plain Python: returns, per strip, the list of
+    (record index, first tile, last tile + 1) pieces the waves write, in wave order."""
+    strips_per_group = n_kv_heads * plan.strips_per_kv_head
+    tiles = [max(1, -(-n // 32)) for n in group_rows]             # per strip of the group
+    first_tile, t = [], 0                                          # of every strip, laid end to end
+    for tl in tiles:
+        for _ in range(strips_per_group):
+            first_tile.append(t)
+            t += tl
+    total = t
+    share = max(-(-total // plan.n_workers), plan.min_share)
+    pieces = [[] for _ in first_tile]
+    strip = 0
+    for w in range(plan.n_workers):
+        lo, hi = w * share, min((w + 1) * share, total)
+        if lo >= total:
+            break
+        while strip + 1 < len(first_tile) and first_tile[strip + 1] <= lo:
+            strip += 1
+        s = strip
+        while s < len(first_tile) and first_tile[s] < hi:
+            n_tiles = tiles[s // strips_per_group]
+            a, b = max(lo, first_tile[s]), min(hi, first_tile[s] + n_tiles)
+            pieces[s].append((w - first_tile[s] // share, a - first_tile[s], b - first_tile[s]))
+            s += 1
+    return pieces, tiles, strips_per_group
+
+
+@pytest.mark.parametrize("seed", range(12))
+def test_balanced_split_never_needs_more_records_than_the_workspace_has(seed):
+    """Safety of the record index: for lengths up to max_ctx_len, however uneven, every piece a wave
+    writes has an index in [0, gh_decode_num_chunks), indices of a strip are consecutive from 0 and
+    its pieces tile [0, tiles) in order.  (A larger index would be a write outside the workspace.)"""
+    import numpy as np
+    rng = np.random.default_rng(1000 + seed)
+    for _ in range(25):
+        T = int(rng.choice([1, 1, 1, 2, 4, 16]))
+        groups = int(rng.choice([1, 2, 3, 17, 64, 300, 1024, 4096]))
+        Hkv = int(rng.choice([1, 2, 8]))
+        G_ = int(rng.choice([1, 4, 8, 20, 40]))
+        max_ctx = int(rng.choice([1, 31, 32, 33, 100, 1000, 4097, 32769]))
+        if groups * T > 8192:
+            groups = 8192 // T
+        p = good(batch=groups * T, n_q_heads=Hkv * G_, n_kv_heads=Hkv, n_slots=max(groups, 1),
+                 slot_capacity=max_ctx, max_ctx_len=max_ctx,
+                 strides=(Hkv * max_ctx * 128, max_ctx * 128, 128), tokens_per_group=T)
+        plan = G.gh_decode_split_plan(p)
+        assert plan.balanced == 1 and plan.n_chunks == G.gh_decode_num_chunks(p)
+        kind = rng.integers(0, 5)
+        if kind == 0:
+            rows = np.full(groups, max_ctx)                       # everything at the limit
+        elif kind == 1:
+            rows = np.zeros(groups, dtype=np.int64)               # one long context among empty ones
+            rows[rng.integers(0, groups)] = max_ctx
+        elif kind == 2:
+            rows = rng.integers(0, max_ctx + 1, size=groups)
+        elif kind == 3:
+            rows = np.where(rng.random(groups) < 0.9, rng.integers(0, 3, size=groups), max_ctx)
+        else:
+            rows = np.minimum(max_ctx, rng.geometric(1.0 / max(1, max_ctx // 8), size=groups))
+        pieces, tiles, spg = _emulate_balanced_split(plan, [int(r) for r in rows], Hkv)
+        for s, ps in enumerate(pieces):
+            assert ps, "a strip nobody visits"
+            assert [rec for rec, _, _ in ps] == list(range(len(ps)))
+            assert len(ps) <= plan.n_chunks, (len(ps), plan.n_chunks, groups, Hkv, G_, T, max_ctx, kind)
+            pos = 0
+            for _, a, b in ps:
+                assert a == pos and b > a
+                pos = b
+            assert pos == tiles[s // spg]
+
+
+def test_split_plan_reports_the_fixed_split_and_checks_its_arguments():
+    p = good(kernel=G.GH_KERNEL_VALU)
+    plan = G.gh_decode_split_plan(p)
+    assert plan.balanced == 0 and plan.n_workers == 0 and plan.n_chunks == G.gh_decode_num_chunks(p)
+    assert G.lib().gh_decode_split_plan(C.byref(p), None) == G.GH_ERR_NULL
+    assert G.lib().gh_decode_split_plan(None, C.byref(G.gh_split_plan())) == G.GH_ERR_NULL
+    two = G.gh_decode_split_plan(good(n_q_heads=64, n_kv_heads=2, strides=(2 * 4097 * 128, 4097 * 128, 128)))
+    assert two.passes_per_strip == 2 and two.strips_per_kv_head == 1 and two.n_workers == 1024
