@@ -119,65 +119,74 @@ __device__ __forceinline__ void load_tile(TileRegs& t, const uint16_t* kbase, co
   }
 }
 
-// One 32-row tile for the 16 head columns.  `lim` is the number of rows the lane's head column
-// attends (rows at or beyond it are masked); columns of one tile may have different limits, and a
-// column may have no row at all in a tile.
-template <bool BF16>
-__device__ __forceinline__ void process_tile(const TileRegs& t, const u32x4 (&qop)[4], f32x4 (&acc)[8],
-                                             float& m, float& l, float scale_log2e, int tile_row0,
-                                             int lim, int c) {
+// One 32-row tile for P passes of 16 head columns each (own Q operand, running state and
+// accumulators per pass; the K operands and the transposed V operands are built once).  `lim` is
+// the number of rows the lane's head column attends (rows at or beyond it are masked); columns of
+// one tile may have different limits, and a column may have no row at all in a tile.
+template <bool BF16, int P>
+__device__ __forceinline__ void process_tile(const TileRegs& t, const u32x4 (&qop)[P][4],
+                                             f32x4 (&acc)[P][8], float (&m)[P], float (&l)[P],
+                                             float scale_log2e, int tile_row0, const int (&lim)[P],
+                                             int c) {
   // scores of head hn against this lane's 8 rows
-  f32x4 s[2];
+  f32x4 s[P][2];
 #pragma unroll
   for (int T = 0; T < 2; ++T) {
-    s[T] = f32x4{0.f, 0.f, 0.f, 0.f};
+#pragma unroll
+    for (int i = 0; i < P; ++i) s[i][T] = f32x4{0.f, 0.f, 0.f, 0.f};
 #pragma unroll
     for (int half = 0; half < 2; ++half) {
       // operand of d step kk: lane (hn, c) holds d-chunk 4kk + c of row rho(T, hn)
       const u32x4 k_even = upper_from_rotated(t.k[T][half][0], t.k[T][half][1]);   // kk = 2*half
       const u32x4 k_odd = lower_from_rotated(t.k[T][half][1], t.k[T][half][0]);    // kk = 2*half + 1
-      s[T] = mfma<BF16>(k_even, qop[2 * half], s[T]);
-      s[T] = mfma<BF16>(k_odd, qop[2 * half + 1], s[T]);
+#pragma unroll
+      for (int i = 0; i < P; ++i) {
+        s[i][T] = mfma<BF16>(k_even, qop[i][2 * half], s[i][T]);
+        s[i][T] = mfma<BF16>(k_odd, qop[i][2 * half + 1], s[i][T]);
+      }
     }
   }
-  float tv[8];
-  float mx = kNegInf;
+  u32x4 p_hi[P], p_lo[P];
 #pragma unroll
-  for (int e = 0; e < 8; ++e) {
-    const int row = tile_row0 + 16 * (e >> 2) + 4 * (e & 3) + c;
-    tv[e] = row < lim ? s[e >> 2][e & 3] * scale_log2e : kNegInf;
-    mx = fmaxf(mx, tv[e]);
-  }
-  mx = fmaxf(mx, xor16(mx));
-  mx = fmaxf(mx, xor32(mx));
-  const float mn = fmaxf(m, mx);
-  // a column that has seen no row yet keeps m = -inf; subtract 0 then, so that every exponent
-  // below is -inf (weight 0) rather than inf - inf
-  const float ref = mn == kNegInf ? 0.f : mn;
-  const float alpha = fast_exp2(m - ref);
-  m = mn;
-  float sum = 0.f;
-  float lo[8];
+  for (int i = 0; i < P; ++i) {
+    float tv[8];
+    float mx = kNegInf;
 #pragma unroll
-  for (int e = 0; e < 8; ++e) {
-    tv[e] = fast_exp2(tv[e] - ref);
-    sum += tv[e];
-  }
-  l = fmaf(l, alpha, sum);
-  u32x4 p_hi, p_lo;
+    for (int e = 0; e < 8; ++e) {
+      const int row = tile_row0 + 16 * (e >> 2) + 4 * (e & 3) + c;
+      tv[e] = row < lim[i] ? s[i][e >> 2][e & 3] * scale_log2e : kNegInf;
+      mx = fmaxf(mx, tv[e]);
+    }
+    mx = fmaxf(mx, xor16(mx));
+    mx = fmaxf(mx, xor32(mx));
+    const float mn = fmaxf(m[i], mx);
+    // a column that has seen no row yet keeps m = -inf; subtract 0 then, so that every exponent
+    // below is -inf (weight 0) rather than inf - inf
+    const float ref = mn == kNegInf ? 0.f : mn;
+    const float alpha = fast_exp2(m[i] - ref);
+    m[i] = mn;
+    float sum = 0.f;
+    float lo[8];
 #pragma unroll
-  for (int w = 0; w < 4; ++w) {
-    const uint32_t hi = pack2<BF16>(tv[2 * w], tv[2 * w + 1]);
-    float h0, h1;
-    unpack2<BF16>(hi, h0, h1);
-    lo[2 * w] = tv[2 * w] - h0;
-    lo[2 * w + 1] = tv[2 * w + 1] - h1;
-    p_hi[w] = hi;
-    p_lo[w] = pack2<BF16>(lo[2 * w], lo[2 * w + 1]);
-  }
-  if (__any(alpha != 1.f)) {
+    for (int e = 0; e < 8; ++e) {
+      tv[e] = fast_exp2(tv[e] - ref);
+      sum += tv[e];
+    }
+    l[i] = fmaf(l[i], alpha, sum);
 #pragma unroll
-    for (int tcol = 0; tcol < 8; ++tcol) acc[tcol] *= alpha;
+    for (int w = 0; w < 4; ++w) {
+      const uint32_t hi = pack2<BF16>(tv[2 * w], tv[2 * w + 1]);
+      float h0, h1;
+      unpack2<BF16>(hi, h0, h1);
+      lo[2 * w] = tv[2 * w] - h0;
+      lo[2 * w + 1] = tv[2 * w + 1] - h1;
+      p_hi[i][w] = hi;
+      p_lo[i][w] = pack2<BF16>(lo[2 * w], lo[2 * w + 1]);
+    }
+    if (__any(alpha != 1.f)) {
+#pragma unroll
+      for (int tcol = 0; tcol < 8; ++tcol) acc[i][tcol] *= alpha;
+    }
   }
   // O^T += V^T P^T, one 16-column tile at a time
 #pragma unroll
@@ -189,8 +198,11 @@ __device__ __forceinline__ void process_tile(const TileRegs& t, const u32x4 (&qo
       const uint32_t even = t.v[2 * w][tcol >> 1], odd = t.v[2 * w + 1][tcol >> 1];
       vt[w] = (tcol & 1) ? ((even >> 16) | (odd & 0xffff0000u)) : ((even & 0xffffu) | (odd << 16));
     }
-    acc[tcol] = mfma<BF16>(vt, p_hi, acc[tcol]);
-    acc[tcol] = mfma<BF16>(vt, p_lo, acc[tcol]);
+#pragma unroll
+    for (int i = 0; i < P; ++i) {
+      acc[i][tcol] = mfma<BF16>(vt, p_hi[i], acc[i][tcol]);
+      acc[i][tcol] = mfma<BF16>(vt, p_lo[i], acc[i][tcol]);
+    }
   }
 }
 
@@ -323,14 +335,15 @@ __device__ __forceinline__ void run_strip(const AttnArgs& a, int b, int g, int p
   const int hn = lane & 15, c = lane >> 4;
 
   // Q operand: d-chunk 4kk + c of head hn (zeros for the padding heads).
-  u32x4 qraw[4], qop[4];
+  u32x4 qraw[4], qop[1][4];
   load_q(qraw, a, b, g, pass, nh, hn, c);
-  keep_real_heads(qop, qraw, nh, hn);
+  keep_real_heads(qop[0], qraw, nh, hn);
 
-  f32x4 acc[8];
+  f32x4 acc[1][8];
 #pragma unroll
-  for (int tcol = 0; tcol < 8; ++tcol) acc[tcol] = f32x4{0.f, 0.f, 0.f, 0.f};
-  float m = kNegInf, l = 0.f;
+  for (int tcol = 0; tcol < 8; ++tcol) acc[0][tcol] = f32x4{0.f, 0.f, 0.f, 0.f};
+  float m[1] = {kNegInf}, l[1] = {0.f};
+  const int lim[1] = {r1};
 
   const uint16_t* kbase = a.k_cache + strip;
   const uint16_t* vbase = a.v_cache + strip;
@@ -343,12 +356,12 @@ __device__ __forceinline__ void run_strip(const AttnArgs& a, int b, int g, int p
   load_tile(ta, kbase, vbase, a, r0, last, hn, c);
   for (int row0 = r0; row0 < r1; row0 += 64) {
     load_tile(tb, kbase, vbase, a, row0 + 32, last, hn, c);
-    process_tile<BF16>(ta, qop, acc, m, l, a.scale_log2e, row0, r1, c);
+    process_tile<BF16, 1>(ta, qop, acc, m, l, a.scale_log2e, row0, lim, c);
     load_tile(ta, kbase, vbase, a, row0 + 64, last, hn, c);
-    if (row0 + 32 < r1) process_tile<BF16>(tb, qop, acc, m, l, a.scale_log2e, row0 + 32, r1, c);
+    if (row0 + 32 < r1) process_tile<BF16, 1>(tb, qop, acc, m, l, a.scale_log2e, row0 + 32, lim, c);
   }
 
-  store_record(a, b, g, pass, nh, slot, acc, m, l, hn, c);
+  store_record(a, b, g, pass, nh, slot, acc[0], m[0], l[0], hn, c);
 }
 
 // Marks partial records [slot0, slot1) of heads h0 .. h0+nh-1 of sequence b as empty.
@@ -607,13 +620,9 @@ __global__ __launch_bounds__(256, P == 1 ? 2 : 1) void attn_mfma_balanced_kernel
 
   // One tile of arithmetic; closes the record when the tile ends this wave's piece of the strip.
   auto compute = [&](const TileRegs& regs) {
-    if (cp.n > 0) {
-#pragma unroll
-      for (int i = 0; i < P; ++i)
-        if (nh[i] > 0)
-          process_tile<BF16>(regs, qop[i], acc[i], m[i], l[i], a.scale_log2e, (int)cp.lt * 32,
-                             lim[i], c);
-    }
+    // (a pass without columns runs on a zero operand; its results are never stored)
+    if (cp.n > 0)
+      process_tile<BF16, P>(regs, qop, acc, m, l, a.scale_log2e, (int)cp.lt * 32, lim, c);
     const bool strip_end = cp.lt + 1 == cp.tiles;
     if (strip_end || cp.t + 1 == t_end) {
       const uint32_t strip_t0 = cp.t - cp.lt;                  // global index of the strip's tile 0
