@@ -248,3 +248,22 @@ def test_split_plan_reports_the_fixed_split_and_checks_its_arguments():
     assert G.lib().gh_decode_split_plan(None, C.byref(G.gh_split_plan())) == G.GH_ERR_NULL
     two = G.gh_decode_split_plan(good(n_q_heads=64, n_kv_heads=2, strides=(2 * 4097 * 128, 4097 * 128, 128)))
     assert two.passes_per_strip == 2 and two.strips_per_kv_head == 1 and two.n_workers == 1024
+
+
+def test_public_headers_are_plain_c(tmp_path):
+    """The boundary is a C ABI: every header under include/ must compile as strict C99 on its own
+    (and as C++), with nothing but <stddef.h> / <stdint.h> behind it."""
+    import shutil
+    import subprocess
+    inc = os.path.join(ROOT, "include")
+    headers = sorted(f for f in os.listdir(inc) if f.endswith(".h"))
+    assert headers == ["gh_sim.h", "gh_slot_pool.h", "gh_tier2.h"]
+    for h in headers:
+        src = tmp_path / (h[:-2] + "_only.c")
+        src.write_text(f'#include "{h}"\nint main(void) {{ return 0; }}\n')
+        for cc, std in (("gcc", ["-std=c99", "-pedantic"]), ("g++", ["-std=c++11", "-x", "c++"])):
+            if shutil.which(cc) is None:
+                pytest.skip(f"{cc} not available")
+            res = subprocess.run([cc, *std, "-Wall", "-Wextra", "-Werror", "-fsyntax-only", "-I", inc,
+                                  str(src)], capture_output=True, text=True)
+            assert res.returncode == 0, f"{h} with {cc}: {res.stderr}"
