@@ -135,3 +135,37 @@ def test_one_allocation_holding_several_layers():
     for layer in range(n_layers):                                        # no layer touched another
         assert np.array_equal(W.bits(k_all[layer]), hosts[layer]["k_cache"])
         assert np.array_equal(W.bits(v_all[layer]), hosts[layer]["v_cache"])
+
+
+def test_batches_at_different_layers_merged_into_one_launch():
+    """A Tier-2 node holds several batches in flight, each waiting at its own layer (Section 3.3).
+    With the layers in one allocation their steps need not be launched one by one: the entries of
+    all of them form one batch whose slot ids are layer * slots_per_layer + slot.  One launch of
+    three 4-sequence batches must give each batch the result of its own step."""
+    n_layers, B, H, Hkv, d = 3, 4, 8, 2, 128
+    lengths = [np.array([100, 5, 300, 64], dtype=np.int32), np.array([0, 31, 32, 257], dtype=np.int32),
+               np.array([319, 1, 77, 200], dtype=np.int32)]
+    layers = []
+    for layer in range(n_layers):
+        w = W.Workload(f"inflight{layer}", B, H, Hkv, d, "bf16", ("const", 0), 95 + layer)
+        layers.append(W.make_inputs(w, DEV, lengths=lengths[layer], n_slots=B, capacity=320))
+    hosts = [Hh.host_copy(x) for x in layers]
+    k_all = torch.stack([x["k_cache"] for x in layers]).contiguous()     # [layer][slot][head][row][d]
+    v_all = torch.stack([x["v_cache"] for x in layers]).contiguous()
+    cat = lambda name: torch.cat([x[name] for x in layers]).contiguous()
+    merged = {"q": cat("q"), "k_new": cat("k_new"), "v_new": cat("v_new"), "pos": cat("pos"),
+              "ctx_len": cat("ctx_len"), "k_cache": k_all, "v_cache": v_all,
+              "slot_id": torch.cat([x["slot_id"] + layer * B for layer, x in enumerate(layers)])}
+    p = G.make_problem(n_layers * B, H, Hkv, d, G.GH_BF16, n_layers * B, 320, 320,
+                       layers[0]["strides"], layers[0]["scale"])
+    ws = G.alloc_workspace(p, DEV)
+    ws.fill_(float("nan"))
+    out = torch.full((n_layers * B, H, d), float("nan"), dtype=torch.float32, device=DEV)
+    G.decode_step(p, merged, ws, out)
+    torch.cuda.synchronize()
+    got = out.cpu().numpy()
+    for layer in range(n_layers):
+        Hh.assert_parity(got[layer * B:(layer + 1) * B], Hh.oracle_step(layers[layer], hosts[layer]),
+                         f"batch at layer {layer}")
+        assert np.array_equal(W.bits(k_all[layer]), hosts[layer]["k_cache"])
+        assert np.array_equal(W.bits(v_all[layer]), hosts[layer]["v_cache"])
