@@ -364,6 +364,55 @@ def test_token_groups_share_the_slot_stream_and_match_the_oracle(H, Hkv, T, dtyp
     assert np.array_equal(W.bits(inp["v_cache"]), host["v_cache"])
 
 
+def test_seeded_sweep_of_token_groups():
+    """Thirty seeded batches of groups: random T, head counts and layouts; every group is a run of
+    consecutive tokens of one prompt (possibly none, possibly not from the group's first row) with
+    padding rows anywhere around it."""
+    rng = np.random.default_rng(20250118)
+    for case in range(30):
+        T = int(rng.choice([2, 3, 4, 8, 16, 33]))
+        Hkv = int(rng.choice([1, 2, 4]))
+        group = int(rng.choice([1, 2, 3, 4, 8, 16]))
+        n_groups = int(rng.choice([1, 2, 5, 20]))
+        layout = str(rng.choice(["head_major", "token_major", "head_blocked"]))
+        dtype = str(rng.choice(["f16", "bf16"]))
+        rows, spare = [], n_groups                       # prompt slots 0 .. n_groups-1, then spares
+        for gidx in range(n_groups):
+            k = int(rng.integers(0, T + 1))              # live tokens in this group
+            first = int(rng.integers(0, T - k + 1))      # padding before them
+            base = int(rng.choice([0, 1, 30, 31, 32, 100, 400]))
+            for t in range(T):
+                if first <= t < first + k:
+                    rows.append((base + t - first, gidx, True))
+                else:
+                    rows.append((0, spare, False))
+                    spare += 1
+        lengths = np.array([r[0] for r in rows], dtype=np.int32)
+        slots = np.array([r[1] for r in rows], dtype=np.int32)
+        live = np.array([r[2] for r in rows])
+        print(f"case {case}: T={T} Hkv={Hkv} group={group} groups={n_groups} {layout} {dtype} "
+              f"rows={len(rows)} live={int(live.sum())}", flush=True)
+        w = W.Workload(f"gsweep{case}", len(rows), Hkv * group, Hkv, 128, dtype, ("const", 0),
+                       8000 + case)
+        inp = W.make_inputs(w, DEV, lengths=lengths, n_slots=spare, capacity=448, slots=slots,
+                            layout=layout, block_rows=64)
+        host = Hh.host_copy(inp)
+        ctx = np.where(live, lengths + 1, 0).astype(np.int32)
+        inp["ctx_len"] = torch.from_numpy(ctx).to(DEV)
+        host["ctx_len"] = ctx
+        want = Hh.oracle_step(inp, host)
+        p = G.problem_from_inputs(inp, tokens_per_group=T)
+        ws = G.alloc_workspace(p, DEV)
+        ws.fill_(float("nan"))
+        out = torch.full((w.batch, Hkv * group, 128), float("nan"), dtype=torch.float32, device=DEV)
+        G.decode_step(p, inp, ws, out)
+        torch.cuda.synchronize()
+        got = out.cpu().numpy()
+        assert not got[~live].any()
+        Hh.assert_parity(got, want, f"group sweep case {case}")
+        assert np.array_equal(W.bits(inp["k_cache"]), host["k_cache"])
+
+
 @pytest.mark.parametrize("layout", ["token_major", "head_blocked"])
 def test_token_groups_on_other_cache_layouts(layout):
     """Grouping and addressing are independent: the same grouped batch on a token-major and on a
