@@ -624,6 +624,29 @@ def test_seeded_sweep_of_shapes_layouts_and_splits():
         assert np.array_equal(W.bits(inp["v_cache"]), host["v_cache"])
 
 
+# ------------------------------------------------------------------ explicit streams
+def test_step_on_an_explicit_stream_while_another_stream_is_busy():
+    """Every call takes the stream it is given: a step issued on a side stream (default priority)
+    while the current stream grinds through unrelated work, then awaited, matches the oracle."""
+    w = small("stream", 5, 8, 2, "bf16", 92)
+    L = np.array([10, 200, 31, 64, 333], dtype=np.int32)
+    inp = W.make_inputs(w, DEV, lengths=L)
+    host = Hh.host_copy(inp)
+    p = G.problem_from_inputs(inp)
+    ws = G.alloc_workspace(p, DEV)
+    out = torch.full((w.batch, w.n_q_heads, w.head_dim), float("nan"), dtype=torch.float32, device=DEV)
+    torch.cuda.synchronize()
+    side = torch.cuda.Stream()
+    busy = torch.randn((2048, 2048), device=DEV)
+    for _ in range(20):
+        busy = busy @ busy.T * 1e-3                      # keeps the current stream occupied
+    G.decode_step(p, inp, ws, out, stream=side)
+    side.synchronize()
+    Hh.assert_parity(out.cpu().numpy(), Hh.oracle_step(inp, host), "side stream")
+    torch.cuda.synchronize()
+    assert torch.isfinite(busy).all()
+
+
 # ------------------------------------------------------------------ HIP graph replay
 @pytest.mark.parametrize("kernel", ["valu", "mfma"])
 def test_step_captured_in_a_hip_graph_replays_with_new_inputs(kernel):
