@@ -97,6 +97,9 @@ def main():
                          "the GB/s printed then counts every row's K/V as if read separately")
     ap.add_argument("--out16", action="store_true",
                     help="experiment: the merge stores the model's 16-bit type (gh_decode_reduce_native)")
+    ap.add_argument("--early", action="store_true",
+                    help="experiment: gh_decode_attention_out (the attention kernel stores the heads "
+                         "one wave covers alone; the merge completes the rest)")
     ap.add_argument("--paged", action="store_true",
                     help="keep the caches in a gh_slot_pool (virtual slots, pages mapped on demand)")
     ap.add_argument("--page-rows", type=int, default=1024)
@@ -203,8 +206,13 @@ def main():
                                inp["slot_id"], inp["pos"], None))
         if events is not None:
             events[0].record()
-        G.check(G.gh_decode_attention(p, inp["q"], inp["k_cache"], inp["v_cache"], inp["slot_id"],
-                                      inp["ctx_len"], ws))
+        if args.early:
+            G.check(G.gh_decode_attention_out(p, inp["q"], inp["k_cache"], inp["v_cache"],
+                                              inp["slot_id"], inp["ctx_len"], ws, out,
+                                              G.GH_OUT_NATIVE if args.out16 else G.GH_OUT_F32))
+        else:
+            G.check(G.gh_decode_attention(p, inp["q"], inp["k_cache"], inp["v_cache"], inp["slot_id"],
+                                          inp["ctx_len"], ws))
         if events is not None:
             events[1].record()
         G.check(reduce(p, ws, inp["ctx_len"], out))
@@ -268,7 +276,7 @@ def main():
                                f"H_kv={w.n_kv_heads}, d={w.head_dim}, lengths={list(w.lengths)}, "
                                f"seed={w.seed}",
                    "kernel": args.kernel, "chunk_rows": chunk_rows, "n_chunks": n_chunks,
-                   "step": "gh_kv_append + gh_decode_attention + "
+                   "step": "gh_kv_append + gh_decode_attention" + ("_out" if args.early else "") + " + "
                            + ("gh_decode_reduce_native" if args.out16 else "gh_decode_reduce"),
                    "paged_slots": paged_info, "hip_graph_ms_per_step": graph_ms,
                    "step_algorithmic_bytes": step_bytes,
@@ -279,7 +287,7 @@ def main():
                      "traffic": args.traffic_bytes if args.traffic_bytes is not None else (
                          MEASURED_TRAFFIC_BYTES.get(w.name)
                          if args.kernel == "auto" and not (args.chunk_rows or args.batch or args.const_len or args.capacity or args.paged
-                                                      or args.mixed or args.prefill or args.group or args.out16)
+                                                      or args.mixed or args.prefill or args.group or args.out16 or args.early)
                          else None),
                      "algorithmic_bytes_per_launch": attn_bytes,
                      "avg_launch_ms": float(attn_ms.mean())},

@@ -148,7 +148,8 @@ const char* gh_status_string(int32_t status);
  * Workspace layout (base 16-byte aligned), with d = head_dim:
  *   float o[B][H][C][d], float m[B][H][C], float l[B][H][C], int32 n[B][H]
  * n = how many of a head's C records are in use (records at index >= n are
- * unspecified and ignored by the merge).
+ * unspecified and ignored by the merge); -1 = the head's result is already in
+ * the output (gh_decode_attention_out).
  * For record c of (sequence b, head h), over the rows r it covers and with
  * t_r = scale * log2(e) * (q . K_r):
  *   m = max_r t_r,  l = sum_r 2^(t_r - m),  o[:] = sum_r 2^(t_r - m) * V_r[:]
@@ -207,6 +208,25 @@ int32_t gh_decode_attention(const gh_problem* p, const void* q,
                             const int32_t* slot_id, const int32_t* ctx_len,
                             void* workspace, size_t workspace_bytes,
                             void* hip_stream);
+
+/*
+ * gh_decode_attention that also finishes what it can.  A head whose rows one
+ * wave covers alone (most heads of a large batch) has nothing to merge: its
+ * result is normalised and stored straight into `out`, and its record count in
+ * the workspace is set to -1, which makes the merges below leave that row of
+ * `out` alone.  out_kind GH_OUT_F32: out is fp32 [B, H, d]; GH_OUT_NATIVE: the
+ * model's 16-bit type, rounded as by gh_decode_reduce_native.  Call the
+ * matching merge afterwards with the same `out` to complete the other heads;
+ * the pair gives bit for bit what gh_decode_attention and the merge give.  With
+ * a fixed split or the vector kernel no head is finished early and the call is
+ * gh_decode_attention.  out: 16-byte aligned.
+ */
+typedef enum { GH_OUT_F32 = 0, GH_OUT_NATIVE = 1 } gh_out_kind;
+int32_t gh_decode_attention_out(const gh_problem* p, const void* q,
+                                const void* k_cache, const void* v_cache,
+                                const int32_t* slot_id, const int32_t* ctx_len,
+                                void* workspace, size_t workspace_bytes,
+                                void* out, int32_t out_kind, void* hip_stream);
 
 /*
  * Merge of the chunk partials (same footnote).  Per (b, h), over the records

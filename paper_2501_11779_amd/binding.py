@@ -22,7 +22,8 @@ GH_DEV_BAD_SLOT, GH_DEV_BAD_POS = 1, 2
 
 EXPORTS = ("gh_status_string", "gh_decode_chunk_rows", "gh_decode_num_chunks",
            "gh_decode_workspace_bytes", "gh_kv_append", "gh_decode_attention", "gh_decode_reduce",
-           "gh_decode_reduce_native", "gh_decode_split_plan")
+           "gh_decode_reduce_native", "gh_decode_split_plan", "gh_decode_attention_out")
+GH_OUT_F32, GH_OUT_NATIVE = 0, 1
 POOL_EXPORTS = ("gh_slot_pool_create", "gh_slot_pool_destroy", "gh_slot_pool_k", "gh_slot_pool_v",
                 "gh_slot_pool_strides", "gh_slot_pool_reserve", "gh_slot_pool_release",
                 "gh_slot_pool_mapped_rows", "gh_slot_pool_get_stats", "gh_slot_pool_blocks")
@@ -97,6 +98,8 @@ def lib():
         L.gh_kv_append.argtypes = [P, V, V, V, V, V, V, V, V]
         L.gh_decode_attention.restype = C.c_int32
         L.gh_decode_attention.argtypes = [P, V, V, V, V, V, V, C.c_size_t, V]
+        L.gh_decode_attention_out.restype = C.c_int32
+        L.gh_decode_attention_out.argtypes = [P, V, V, V, V, V, V, C.c_size_t, V, C.c_int32, V]
         L.gh_decode_reduce.restype = C.c_int32
         L.gh_decode_reduce.argtypes = [P, V, V, V, V]
         L.gh_decode_reduce_native.restype = C.c_int32
@@ -182,6 +185,15 @@ def gh_decode_attention(p, q, k_cache, v_cache, slot_id, ctx_len, workspace, wor
                                      workspace_bytes, _stream(stream))
 
 
+def gh_decode_attention_out(p, q, k_cache, v_cache, slot_id, ctx_len, workspace, out, out_kind,
+                            workspace_bytes=None, stream=None):
+    if workspace_bytes is None:
+        workspace_bytes = workspace.numel() * workspace.element_size()
+    return lib().gh_decode_attention_out(C.byref(p), _ptr(q), _ptr(k_cache), _ptr(v_cache),
+                                         _ptr(slot_id), _ptr(ctx_len), _ptr(workspace),
+                                         workspace_bytes, _ptr(out), int(out_kind), _stream(stream))
+
+
 def gh_decode_reduce(p, workspace, ctx_len, out, stream=None):
     return lib().gh_decode_reduce(C.byref(p), _ptr(workspace), _ptr(ctx_len), _ptr(out),
                                   _stream(stream))
@@ -221,14 +233,22 @@ def alloc_workspace(p, device="cuda"):
     return torch.empty(max(n // 4, 1), dtype=torch.float32, device=device)
 
 
-def decode_step(p, inp, workspace, out, dev_status=None, stream=None, append=True):
-    """append -> attention -> reduce on one stream; raises on a host-side error."""
+def decode_step(p, inp, workspace, out, dev_status=None, stream=None, append=True, early=False):
+    """append -> attention -> reduce on one stream; raises on a host-side error.  `out` is fp32 or
+    the problem's 16-bit type; `early` lets the attention kernel store the heads it can finish."""
+    native = out.dtype != torch.float32
     if append:
         check(gh_kv_append(p, inp["k_cache"], inp["v_cache"], inp["k_new"], inp["v_new"],
                            inp["slot_id"], inp["pos"], dev_status, stream))
-    check(gh_decode_attention(p, inp["q"], inp["k_cache"], inp["v_cache"], inp["slot_id"],
-                              inp["ctx_len"], workspace, None, stream))
-    check(gh_decode_reduce(p, workspace, inp["ctx_len"], out, stream))
+    if early:
+        check(gh_decode_attention_out(p, inp["q"], inp["k_cache"], inp["v_cache"], inp["slot_id"],
+                                      inp["ctx_len"], workspace, out,
+                                      GH_OUT_NATIVE if native else GH_OUT_F32, None, stream))
+    else:
+        check(gh_decode_attention(p, inp["q"], inp["k_cache"], inp["v_cache"], inp["slot_id"],
+                                  inp["ctx_len"], workspace, None, stream))
+    check((gh_decode_reduce_native if native else gh_decode_reduce)(p, workspace, inp["ctx_len"],
+                                                                    out, stream))
     return out
 
 

@@ -274,6 +274,16 @@ __device__ __forceinline__ void swap_lane_bit4(f32x4& lo, f32x4& hi) {
 //        head   (L & 3) + 4 r0 + 8 r1,    chunk  (L >> 2) & 7  of column block  r2 + 2 (L >> 5),
 //    so the eight lanes that differ in bits 2-4 write one whole 128-byte line per instruction;
 //  * write-through stores (see below).
+__device__ __forceinline__ void whole_line_chunks(f32x4 (&x)[8]) {
+#pragma unroll
+  for (int q = 0; q < 8; q += 2) swap_lane_bit2(x[q], x[q + 1]);
+#pragma unroll
+  for (int q = 0; q < 8; ++q)
+    if (!(q & 2)) swap_lane_bit3(x[q], x[q + 2]);
+#pragma unroll
+  for (int q = 0; q < 4; ++q) swap_lane_bit4(x[q], x[q + 4]);
+}
+
 __device__ __forceinline__ void store_record(const AttnArgs& a, int b, int g, int pass, int nh,
                                              int slot, const f32x4 (&acc)[8], float m, float l,
                                              int hn, int c) {
@@ -286,13 +296,7 @@ __device__ __forceinline__ void store_record(const AttnArgs& a, int b, int g, in
     x[2 * i] = f32x4{acc[0][i], acc[1][i], acc[2][i], acc[3][i]};
     x[2 * i + 1] = f32x4{acc[4][i], acc[5][i], acc[6][i], acc[7][i]};
   }
-#pragma unroll
-  for (int q = 0; q < 8; q += 2) swap_lane_bit2(x[q], x[q + 1]);
-#pragma unroll
-  for (int q = 0; q < 8; ++q)
-    if (!(q & 2)) swap_lane_bit3(x[q], x[q + 2]);
-#pragma unroll
-  for (int q = 0; q < 4; ++q) swap_lane_bit4(x[q], x[q + 4]);
+  whole_line_chunks(x);
 
   // Write-through stores (sc0 sc1): among the store policies this one disturbs the read stream
   // least (a streaming-read probe that writes 4 KiB per wave now and then: 7.0 TB/s without stores,
@@ -324,6 +328,57 @@ __device__ __forceinline__ void store_record(const AttnArgs& a, int b, int g, in
     const int64_t pi = column_index(a, b, g, pass, hn) * a.n_chunks + slot;
     a.ws_m[pi] = m;
     a.ws_l[pi] = l;
+  }
+}
+
+// Final result of head columns whose rows this wave covered alone: o / l (zeros for a column
+// without rows), stored straight into the output -- what the merge would compute from this one
+// record, bit for bit (its weight is 2^0) -- in fp32 or rounded once to the 16-bit type.
+template <bool BF16>
+__device__ __forceinline__ void store_final(const AttnArgs& a, int b, int g, int pass, int nh,
+                                            const f32x4 (&acc)[8], float l, int hn, int c) {
+  typedef uint32_t u32x2 __attribute__((ext_vector_type(2)));
+  l += xor16(l);
+  l += xor32(l);
+  f32x4 x[8];
+#pragma unroll
+  for (int i = 0; i < 4; ++i) {
+    x[2 * i] = f32x4{acc[0][i], acc[1][i], acc[2][i], acc[3][i]};
+    x[2 * i + 1] = f32x4{acc[4][i], acc[5][i], acc[6][i], acc[7][i]};
+  }
+#pragma unroll
+  for (int q = 0; q < 8; ++q)
+#pragma unroll
+    for (int e = 0; e < 4; ++e)            // (+ 0: the merge's 1 * o + 0 turns a -0 into +0)
+      x[q][e] = l > 0.f ? (x[q][e] + 0.f) / l : 0.f;
+  whole_line_chunks(x);
+
+  const int lane = 16 * c + hn;
+  const bool wide = a.out_kind == 1;                         // fp32, else the 16-bit type
+  const int esize = wide ? 4 : 2;
+  const int64_t first = column_index(a, b, g, pass, 0);
+  const int64_t last = column_index(a, b, g, pass, nh - 1);
+  char* base = static_cast<char*>(a.out) + first * kHeadDim * esize;
+  const __amdgpu_buffer_rsrc_t dst = __builtin_amdgcn_make_buffer_rsrc(
+      base, 0, (int)((last - first + 1) * kHeadDim * esize), kRawBufferFlags);
+  const int col = 64 * (lane >> 5) + 4 * ((lane >> 2) & 7);
+#pragma unroll
+  for (int k = 0; k < 4; ++k) {
+    const int head = (lane & 3) + 4 * k;
+    if (head < nh) {
+      const int at = (int)((column_index(a, b, g, pass, head) - first) * kHeadDim + col);
+      if (wide) {
+        __builtin_amdgcn_raw_buffer_store_b128(__builtin_bit_cast(u32x4, x[k]), dst, at * 4, 0,
+                                               kWriteThrough);
+        __builtin_amdgcn_raw_buffer_store_b128(__builtin_bit_cast(u32x4, x[k + 4]), dst,
+                                               (at + 32) * 4, 0, kWriteThrough);
+      } else {
+        const u32x2 lo = {pack2<BF16>(x[k][0], x[k][1]), pack2<BF16>(x[k][2], x[k][3])};
+        const u32x2 hi = {pack2<BF16>(x[k + 4][0], x[k + 4][1]), pack2<BF16>(x[k + 4][2], x[k + 4][3])};
+        __builtin_amdgcn_raw_buffer_store_b64(lo, dst, at * 2, 0, kWriteThrough);
+        __builtin_amdgcn_raw_buffer_store_b64(hi, dst, (at + 32) * 2, 0, kWriteThrough);
+      }
+    }
   }
 }
 
@@ -628,10 +683,17 @@ __global__ __launch_bounds__(256, P == 1 ? 2 : 1) void attn_mfma_balanced_kernel
       const uint32_t strip_t0 = cp.t - cp.lt;                  // global index of the strip's tile 0
       int rec = (int)(gw - strip_t0 / share);
       if (cp.n > 0) {
+        // the strip began inside this wave's share and ends here: nothing to merge
+        const bool whole = a.out_kind != 0 && strip_end && strip_t0 >= t0;
 #pragma unroll
-        for (int i = 0; i < P; ++i)
-          if (nh[i] > 0) store_record(a, cp.b, g, pass0 + i, nh[i], rec, acc[i], m[i], l[i], hn, c);
-        ++rec;
+        for (int i = 0; i < P; ++i) {
+          if (nh[i] == 0) continue;
+          if (whole)
+            store_final<BF16>(a, cp.b, g, pass0 + i, nh[i], acc[i], l[i], hn, c);
+          else
+            store_record(a, cp.b, g, pass0 + i, nh[i], rec, acc[i], m[i], l[i], hn, c);
+        }
+        rec = whole ? -1 : rec + 1;
       }
       if (strip_end && c == 0) {                               // records in use for these heads
 #pragma unroll

@@ -34,6 +34,8 @@ struct AttnArgs {
   int32_t batch;
   int32_t n_workers, min_share;                   // balanced split: waves, least tiles per wave
   float scale_log2e;                              // scale * log2(e)
+  void* out;                                      // final results of heads one wave covers alone
+  int32_t out_kind;                               // 0 none, 1 fp32, 2 binary16, 3 bfloat16
 };
 
 // Offset of row r inside a (slot, head) strip.  Blocked layouts place block r >> shift at that

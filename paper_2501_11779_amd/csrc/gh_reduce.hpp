@@ -47,7 +47,8 @@ __global__ __launch_bounds__(256) void decode_reduce_kernel(const ReduceArgs a) 
   const int ch = lane < a.n_chunks ? lane : 0;
   const float mh = m[ch], lh = l[ch];
   int used = a.ws_n[row];
-  used = used < 0 ? 0 : used < a.n_chunks ? used : a.n_chunks;
+  if (used < 0) return;                        // the attention kernel has stored this row already
+  used = used < a.n_chunks ? used : a.n_chunks;
 
   float2 acc = make_float2(0.f, 0.f);
   if (used <= 2) {

@@ -257,9 +257,15 @@ int32_t gh_kv_append(const gh_problem* p, void* k_cache, void* v_cache, const vo
   return hipGetLastError() == hipSuccess ? GH_OK : GH_ERR_HIP;
 }
 
-int32_t gh_decode_attention(const gh_problem* p, const void* q, const void* k_cache,
-                            const void* v_cache, const int32_t* slot_id, const int32_t* ctx_len,
-                            void* workspace, size_t workspace_bytes, void* hip_stream) {
+}  // extern "C"
+
+namespace {
+
+// out_kind: 0 = no early results, 1 = fp32, 2 = the problem's 16-bit type
+int32_t launch_attention(const gh_problem* p, const void* q, const void* k_cache,
+                         const void* v_cache, const int32_t* slot_id, const int32_t* ctx_len,
+                         void* workspace, size_t workspace_bytes, void* out, int out_kind,
+                         void* hip_stream) {
   const int32_t st = check_problem(p);
   if (st != GH_OK) return st;
   if (p->batch == 0) return GH_OK;
@@ -307,6 +313,8 @@ int32_t gh_decode_attention(const gh_problem* p, const void* q, const void* k_ca
   a.n_workers = pl.n_workers;
   a.min_share = pl.min_share;
   a.scale_log2e = p->scale * 1.44269504088896340736f;
+  a.out = out;
+  a.out_kind = out_kind == 0 ? 0 : out_kind == 1 ? 1 : p->dtype == GH_F16 ? 2 : 3;
 
   hipStream_t s = static_cast<hipStream_t>(hip_stream);
   const bool bf16 = p->dtype == GH_BF16;
@@ -349,10 +357,6 @@ int32_t gh_decode_attention(const gh_problem* p, const void* q, const void* k_ca
   return hipGetLastError() == hipSuccess ? GH_OK : GH_ERR_HIP;
 }
 
-}  // extern "C"
-
-namespace {
-
 // out_kind: 0 = fp32, 1 = the problem's 16-bit type
 int32_t launch_reduce(const gh_problem* p, const void* workspace, void* out, int out_kind,
                       void* hip_stream) {
@@ -385,6 +389,30 @@ int32_t launch_reduce(const gh_problem* p, const void* workspace, void* out, int
 }  // namespace
 
 extern "C" {
+
+int32_t gh_decode_attention(const gh_problem* p, const void* q, const void* k_cache,
+                            const void* v_cache, const int32_t* slot_id, const int32_t* ctx_len,
+                            void* workspace, size_t workspace_bytes, void* hip_stream) {
+  return launch_attention(p, q, k_cache, v_cache, slot_id, ctx_len, workspace, workspace_bytes,
+                          nullptr, 0, hip_stream);
+}
+
+int32_t gh_decode_attention_out(const gh_problem* p, const void* q, const void* k_cache,
+                                const void* v_cache, const int32_t* slot_id, const int32_t* ctx_len,
+                                void* workspace, size_t workspace_bytes, void* out,
+                                int32_t out_kind, void* hip_stream) {
+  if (out_kind != GH_OUT_F32 && out_kind != GH_OUT_NATIVE) return GH_ERR_UNSUPPORTED;
+  const int32_t st = check_problem(p);
+  if (st != GH_OK) return st;
+  if (p->batch == 0) return GH_OK;
+  if (!out) return GH_ERR_NULL;
+  if (!aligned16(out)) return GH_ERR_UNSUPPORTED;
+  // one row of `out` is addressed with 32-bit byte offsets from the first of its (group, kv head)
+  if ((int64_t)tokens_per_group(p) * p->n_q_heads * gh::kHeadDim * 4 > 0x7fffffff)
+    return GH_ERR_UNSUPPORTED;
+  return launch_attention(p, q, k_cache, v_cache, slot_id, ctx_len, workspace, workspace_bytes,
+                          out, out_kind == GH_OUT_F32 ? 1 : 2, hip_stream);
+}
 
 int32_t gh_decode_reduce(const gh_problem* p, const void* workspace, const int32_t* ctx_len,
                          float* out, void* hip_stream) {

@@ -267,3 +267,16 @@ def test_public_headers_are_plain_c(tmp_path):
             res = subprocess.run([cc, *std, "-Wall", "-Wextra", "-Werror", "-fsyntax-only", "-I", inc,
                                   str(src)], capture_output=True, text=True)
             assert res.returncode == 0, f"{h} with {cc}: {res.stderr}"
+
+
+def test_attention_out_checks_its_arguments():
+    p = good()
+    a = 4096
+    assert G.gh_decode_attention_out(p, a, a, a, a, a, a, None, G.GH_OUT_F32, 1 << 40, 0) == G.GH_ERR_NULL
+    assert G.gh_decode_attention_out(p, a, a, a, a, a, a, a + 4, G.GH_OUT_F32, 1 << 40, 0) \
+        == G.GH_ERR_UNSUPPORTED
+    assert G.gh_decode_attention_out(p, a, a, a, a, a, a, a, 7, 1 << 40, 0) == G.GH_ERR_UNSUPPORTED
+    assert G.gh_decode_attention_out(p, a, a, a, a, a, a, a, G.GH_OUT_NATIVE, 16, 0) == G.GH_ERR_WORKSPACE
+    assert G.gh_decode_attention_out(good(batch=0), None, None, None, None, None, None, None,
+                                     G.GH_OUT_F32, 0, 0) == G.GH_OK
+

@@ -624,6 +624,59 @@ def test_seeded_sweep_of_shapes_layouts_and_splits():
         assert np.array_equal(W.bits(inp["v_cache"]), host["v_cache"])
 
 
+# ------------------------------------------------------------------ heads finished by the attention kernel
+@pytest.mark.parametrize("native", [False, True])
+@pytest.mark.parametrize("case", ["ragged", "groups", "large"])
+def test_attention_out_plus_merge_is_bit_identical_to_attention_plus_merge(case, native):
+    """gh_decode_attention_out stores the heads one wave covers alone and marks them; the merge
+    completes the rest.  The pair must give the same bits as attention + merge, in fp32 and in the
+    16-bit type, and must really have finished heads early where strips are short."""
+    tpg = 0
+    if case == "ragged":
+        w = small("early", 40, 8, 2, "bf16", 93)
+        L = np.random.default_rng(5).integers(0, 500, size=40).astype(np.int32)
+        L[:3] = [0, 31, 32]
+        inp = W.make_inputs(w, DEV, lengths=L)
+        ctx = None
+    elif case == "groups":
+        tpg = 4
+        rows = _grouped_rows(tpg)
+        L = np.array([r[0] for r in rows], dtype=np.int32)
+        slots = np.array([r[1] for r in rows], dtype=np.int32)
+        live = np.array([r[2] for r in rows])
+        w = small("earlyg", len(rows), 16, 2, "f16", 94)              # 32 head columns: two passes
+        inp = W.make_inputs(w, DEV, lengths=L, n_slots=int(slots.max()) + 1, capacity=704, slots=slots)
+        ctx = np.where(live, L + 1, 0).astype(np.int32)
+    else:
+        w = W.Workload("earlyl", 1500, 8, 2, 128, "bf16", ("uniform", 0, 300), 95)   # many short strips
+        inp = W.make_inputs(w, DEV)
+        ctx = None
+    host = Hh.host_copy(inp)
+    if ctx is not None:
+        inp["ctx_len"] = torch.from_numpy(ctx).to(DEV)
+        host["ctx_len"] = ctx
+    p = G.problem_from_inputs(inp, tokens_per_group=tpg)
+    dt = W.TORCH_DTYPE[w.dtype] if native else torch.float32
+    outs = []
+    for early in (False, True):
+        ws = G.alloc_workspace(p, DEV)
+        ws.fill_(float("nan"))
+        out = torch.full((w.batch, w.n_q_heads, 128), float("nan"), dtype=dt, device=DEV)
+        G.decode_step(p, inp, ws, out, append=not early, early=early)
+        torch.cuda.synchronize()
+        outs.append(out)
+        n_rec = ws.view(torch.int32)[-w.batch * w.n_q_heads:].cpu().numpy()
+        if early:
+            assert (n_rec == -1).mean() > (0.5 if case == "large" else 0.0)
+        else:
+            assert (n_rec >= 0).all()
+    a, b = outs[0].cpu(), outs[1].cpu()
+    assert torch.equal(a.view(torch.int32 if not native else torch.int16),
+                       b.view(torch.int32 if not native else torch.int16))
+    if not native:
+        Hh.assert_parity(b.numpy(), Hh.oracle_step(inp, host), f"early {case}")
+
+
 # ------------------------------------------------------------------ explicit streams
 def test_step_on_an_explicit_stream_while_another_stream_is_busy():
     """Every call takes the stream it is given: a step issued on a side stream (default priority)
