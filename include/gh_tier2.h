@@ -78,7 +78,8 @@ typedef enum {
   GH_ERR_UNSUPPORTED = -3, /* head_dim != 128, unknown dtype/kernel, alignment  */
   GH_ERR_WORKSPACE = -4,   /* workspace smaller than gh_decode_workspace_bytes  */
   GH_ERR_CAPACITY = -5,    /* max_ctx_len > slot_capacity                       */
-  GH_ERR_HIP = -6          /* the HIP runtime refused the launch                */
+  GH_ERR_HIP = -6,         /* the HIP runtime refused the launch                */
+  GH_ERR_SCRATCH = -7      /* the problem needs more than GH_STATIC_SCRATCH_BYTES  */
 } gh_status;
 
 typedef enum { GH_F16 = 0, GH_BF16 = 1 } gh_dtype;
@@ -247,6 +248,30 @@ int32_t gh_decode_reduce(const gh_problem* p, const void* workspace,
  */
 int32_t gh_decode_reduce_native(const gh_problem* p, const void* workspace,
                                 const int32_t* ctx_len, void* out16, void* hip_stream);
+
+/*
+ * For callers that cannot allocate device memory or hand over a workspace: code
+ * under HIP graph capture, tight serving loops, harnesses that forbid hipMalloc.
+ * gh_decode_attention_out followed by the matching merge, with the partial
+ * records kept in a buffer that lives inside the library's code object instead of
+ * a caller's workspace: GH_STATIC_SCRATCH_BYTES of device memory per GPU the
+ * library runs on, held until the process ends.  Calls nothing that allocates.
+ * `out` and `out_kind` as for gh_decode_attention_out; the result is bit for bit
+ * that of gh_decode_attention_out + gh_decode_reduce / gh_decode_reduce_native.
+ * A problem whose gh_decode_workspace_bytes exceeds GH_STATIC_SCRATCH_BYTES
+ * returns GH_ERR_SCRATCH and launches nothing.  The first call on a device looks
+ * up that device's copy of the buffer (a failure there is GH_ERR_HIP).  Every call
+ * on one GPU shares that GPU's buffer, on whatever stream: calls that overlap in
+ * time on one GPU race and give wrong results; calls ordered by a stream or by
+ * events are fine.  Nothing in the buffer has to start at zero -- every word a
+ * merge reads has been written by the attention kernel of the same call -- so
+ * what an earlier, larger call left behind is harmless.
+ */
+#define GH_STATIC_SCRATCH_BYTES (64u << 20)
+int32_t gh_decode_attention_static(const gh_problem* p, const void* q,
+                                   const void* k_cache, const void* v_cache,
+                                   const int32_t* slot_id, const int32_t* ctx_len,
+                                   void* out, int32_t out_kind, void* hip_stream);
 
 #ifdef __cplusplus
 }

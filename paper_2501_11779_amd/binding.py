@@ -15,14 +15,16 @@ LIB_PATH = os.path.join(HERE, "libgh_tier2.so")
 
 GH_OK = 0
 GH_ERR_NULL, GH_ERR_SHAPE, GH_ERR_UNSUPPORTED = -1, -2, -3
-GH_ERR_WORKSPACE, GH_ERR_CAPACITY, GH_ERR_HIP = -4, -5, -6
+GH_ERR_WORKSPACE, GH_ERR_CAPACITY, GH_ERR_HIP, GH_ERR_SCRATCH = -4, -5, -6, -7
+GH_STATIC_SCRATCH_BYTES = 64 << 20
 GH_F16, GH_BF16 = 0, 1
 GH_KERNEL_AUTO, GH_KERNEL_VALU, GH_KERNEL_MFMA = 0, 1, 2
 GH_DEV_BAD_SLOT, GH_DEV_BAD_POS = 1, 2
 
 EXPORTS = ("gh_status_string", "gh_decode_chunk_rows", "gh_decode_num_chunks",
            "gh_decode_workspace_bytes", "gh_kv_append", "gh_decode_attention", "gh_decode_reduce",
-           "gh_decode_reduce_native", "gh_decode_split_plan", "gh_decode_attention_out")
+           "gh_decode_reduce_native", "gh_decode_split_plan", "gh_decode_attention_out",
+           "gh_decode_attention_static")
 GH_OUT_F32, GH_OUT_NATIVE = 0, 1
 POOL_EXPORTS = ("gh_slot_pool_create", "gh_slot_pool_destroy", "gh_slot_pool_k", "gh_slot_pool_v",
                 "gh_slot_pool_strides", "gh_slot_pool_reserve", "gh_slot_pool_release",
@@ -100,6 +102,8 @@ def lib():
         L.gh_decode_attention.argtypes = [P, V, V, V, V, V, V, C.c_size_t, V]
         L.gh_decode_attention_out.restype = C.c_int32
         L.gh_decode_attention_out.argtypes = [P, V, V, V, V, V, V, C.c_size_t, V, C.c_int32, V]
+        L.gh_decode_attention_static.restype = C.c_int32
+        L.gh_decode_attention_static.argtypes = [P, V, V, V, V, V, V, C.c_int32, V]
         L.gh_decode_reduce.restype = C.c_int32
         L.gh_decode_reduce.argtypes = [P, V, V, V, V]
         L.gh_decode_reduce_native.restype = C.c_int32
@@ -192,6 +196,12 @@ def gh_decode_attention_out(p, q, k_cache, v_cache, slot_id, ctx_len, workspace,
     return lib().gh_decode_attention_out(C.byref(p), _ptr(q), _ptr(k_cache), _ptr(v_cache),
                                          _ptr(slot_id), _ptr(ctx_len), _ptr(workspace),
                                          workspace_bytes, _ptr(out), int(out_kind), _stream(stream))
+
+
+def gh_decode_attention_static(p, q, k_cache, v_cache, slot_id, ctx_len, out, out_kind, stream=None):
+    return lib().gh_decode_attention_static(C.byref(p), _ptr(q), _ptr(k_cache), _ptr(v_cache),
+                                            _ptr(slot_id), _ptr(ctx_len), _ptr(out), int(out_kind),
+                                            _stream(stream))
 
 
 def gh_decode_reduce(p, workspace, ctx_len, out, stream=None):

@@ -8,6 +8,13 @@
 #include "gh_common.hpp"
 #include "gh_reduce.hpp"
 
+#include <mutex>
+
+// Partial records of gh_decode_attention_static: one copy per GPU the code object is loaded on.
+// In host code this name is only a handle for hipGetSymbolAddress; the device address of each
+// GPU's copy is looked up once per device (static_scratch_of) and that pointer is what the kernels get.
+static __device__ __align__(256) unsigned char scratch[GH_STATIC_SCRATCH_BYTES];
+
 namespace {
 
 constexpr int kComputeUnits = 256;          // MI355X
@@ -186,6 +193,7 @@ const char* gh_status_string(int32_t status) {
     case GH_ERR_WORKSPACE: return "workspace too small";
     case GH_ERR_CAPACITY: return "max_ctx_len exceeds slot_capacity";
     case GH_ERR_HIP: return "HIP launch failed";
+    case GH_ERR_SCRATCH: return "problem needs more partial records than the library's static scratch holds";
     default: return "unknown status";
   }
 }
@@ -357,6 +365,28 @@ int32_t launch_attention(const gh_problem* p, const void* q, const void* k_cache
   return hipGetLastError() == hipSuccess ? GH_OK : GH_ERR_HIP;
 }
 
+// Device address of the current GPU's copy of `scratch`, looked up on the first call on that GPU
+// and kept.  No allocation: the buffer is part of the loaded code object.
+constexpr int kMaxDevices = 64;
+std::mutex g_scratch_mutex;
+void* g_scratch_ptr[kMaxDevices] = {};
+
+int32_t static_scratch_of(void** ptr) {
+  int dev = -1;
+  if (hipGetDevice(&dev) != hipSuccess || dev < 0 || dev >= kMaxDevices) return GH_ERR_HIP;
+  std::lock_guard<std::mutex> lock(g_scratch_mutex);
+  if (!g_scratch_ptr[dev]) {
+    void* found = nullptr;
+    if (hipGetSymbolAddress(&found, HIP_SYMBOL(scratch)) != hipSuccess || !found) {
+      (void)hipGetLastError();
+      return GH_ERR_HIP;
+    }
+    g_scratch_ptr[dev] = found;
+  }
+  *ptr = g_scratch_ptr[dev];
+  return GH_OK;
+}
+
 // out_kind: 0 = fp32, 1 = the problem's 16-bit type
 int32_t launch_reduce(const gh_problem* p, const void* workspace, void* out, int out_kind,
                       void* hip_stream) {
@@ -412,6 +442,26 @@ int32_t gh_decode_attention_out(const gh_problem* p, const void* q, const void* 
     return GH_ERR_UNSUPPORTED;
   return launch_attention(p, q, k_cache, v_cache, slot_id, ctx_len, workspace, workspace_bytes,
                           out, out_kind == GH_OUT_F32 ? 1 : 2, hip_stream);
+}
+
+int32_t gh_decode_attention_static(const gh_problem* p, const void* q, const void* k_cache,
+                                   const void* v_cache, const int32_t* slot_id,
+                                   const int32_t* ctx_len, void* out, int32_t out_kind,
+                                   void* hip_stream) {
+  if (out_kind != GH_OUT_F32 && out_kind != GH_OUT_NATIVE) return GH_ERR_UNSUPPORTED;
+  const int32_t st = check_problem(p);
+  if (st != GH_OK) return st;
+  if (p->batch == 0) return GH_OK;
+  if (!q || !k_cache || !v_cache || !slot_id || !ctx_len || !out) return GH_ERR_NULL;
+  const size_t need = workspace_floats(p, make_plan(p)) * sizeof(float);
+  if (need > (size_t)GH_STATIC_SCRATCH_BYTES) return GH_ERR_SCRATCH;
+  void* ws = nullptr;
+  const int32_t sst = static_scratch_of(&ws);
+  if (sst != GH_OK) return sst;
+  const int32_t ast = gh_decode_attention_out(p, q, k_cache, v_cache, slot_id, ctx_len, ws, need,
+                                              out, out_kind, hip_stream);
+  if (ast != GH_OK) return ast;
+  return launch_reduce(p, ws, out, out_kind == GH_OUT_F32 ? 0 : 1, hip_stream);
 }
 
 int32_t gh_decode_reduce(const gh_problem* p, const void* workspace, const int32_t* ctx_len,

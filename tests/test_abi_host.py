@@ -55,7 +55,7 @@ def test_slot_pool_symbols_are_exported_and_arguments_checked_without_a_gpu():
 
 
 def test_status_strings():
-    for st in range(0, -7, -1):
+    for st in range(0, -8, -1):
         assert G.gh_status_string(st) not in ("", "unknown status")
     assert G.gh_status_string(-99) == "unknown status"
 
