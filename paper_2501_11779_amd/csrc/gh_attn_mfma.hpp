@@ -724,7 +724,8 @@ __global__ __launch_bounds__(256, P == 1 ? 2 : 1) void attn_mfma_balanced_kernel
           } else {
 #pragma unroll
             for (int i = 0; i < P; ++i) {
-              load_q(qnext[i], a, qb, qg, qpass0 + i, qnext_nh[i], hn, c);
+              // (a pass without columns fetches the first pass's rows, as fetch() does)
+              load_q(qnext[i], a, qb, qg, qnext_nh[i] > 0 ? qpass0 + i : qpass0, qnext_nh[i], hn, c);
               lnext[i] = Limit{0, more ? qs.n : cp.n};
             }
           }

@@ -13,34 +13,7 @@ pytestmark = pytest.mark.gpu
 DEV = "cuda"
 
 
-def round_f64_to_bits(x, dtype):
-    """Correctly rounded (nearest, ties to even) 16-bit patterns of float64 values, without going
-    through float32: the two neighbours in the 16-bit format are compared in float64."""
-    x = np.asarray(x, dtype=np.float64)
-    if dtype == "f16":
-        return x.astype(np.float16).view(np.uint16)
-    f32 = x.astype(np.float32)
-    trunc = (f32.view(np.uint32) & 0xffff0000).astype(np.uint32)       # toward zero, 8-bit mantissa
-    lo = trunc.view(np.float32).astype(np.float64)
-    hi = (trunc + np.uint32(0x10000)).view(np.float32).astype(np.float64)  # next away from zero
-    # float32 rounding may have carried past hi's neighbour; restart from the value below |x|
-    swap = np.abs(lo) > np.abs(x)
-    trunc = np.where(swap, trunc - np.uint32(0x10000), trunc).astype(np.uint32)
-    lo = trunc.view(np.float32).astype(np.float64)
-    hi = (trunc + np.uint32(0x10000)).view(np.float32).astype(np.float64)
-    dlo, dhi = np.abs(x - lo), np.abs(hi - x)
-    even_lo = ((trunc >> 16) & 1) == 0
-    pick_hi = (dhi < dlo) | ((dhi == dlo) & ~even_lo)
-    bits = np.where(pick_hi, trunc + np.uint32(0x10000), trunc) >> 16
-    return bits.astype(np.uint16)
-
-
-def ulps_apart(a_bits, b_bits):
-    """Distance in representable values between two arrays of same-sign-or-zero 16-bit patterns."""
-    def key(u):
-        u = u.astype(np.int32)
-        return np.where(u & 0x8000, -(u & 0x7fff), u & 0x7fff)
-    return np.abs(key(a_bits) - key(b_bits))
+round_f64_to_bits, ulps_apart = Hh.round_f64_to_bits, Hh.ulps_apart
 
 
 @pytest.mark.parametrize("dtype", ["f16", "bf16"])
