@@ -24,9 +24,23 @@ if ROOT not in sys.path:
 HBM_PEAK_GBS = 8000.0   # MI355X published HBM3E peak
 
 # HBM bytes per gh_decode_attention launch (FETCH_SIZE + WRITE_SIZE, each scaled by what the same
-# counter reads for a plain 1 GiB device copy) from the rocprofv3 --pmc runs summarised in
-# profiles/gh_decode_attention_<workload>.md; valid for the library's default kernel and split.
-MEASURED_TRAFFIC_BYTES = {"c2": 1330104531, "c3": 2714920191, "c4": 9248076659, "c5": 2250269880}
+# counter reads for a plain 1 GiB device copy) are read from profiles/traffic.json, which
+# `python -m paper_2501_11779_amd.profile` writes together with the rocprofv3 summaries in
+# profiles/; they are valid for the library's default kernel and split only.
+TRAFFIC_FILE = os.path.join(ROOT, "profiles", "traffic.json")
+
+
+def measured_traffic(name):
+    """(bytes per attention launch, where the figure comes from) or (None, None)."""
+    try:
+        with open(TRAFFIC_FILE) as fh:
+            rec = json.load(fh)[name]
+        return rec["attention_bytes_per_launch"], (
+            f"profiles/traffic.json: rocprofv3 --pmc FETCH_SIZE / WRITE_SIZE on {rec['kernel']}, "
+            f"scaled by a 1 GiB device copy (factors {rec['fetch_factor']:.4f} / "
+            f"{rec['write_factor']:.4f}); summary {rec['summary']}")
+    except (OSError, KeyError, ValueError):
+        return None, None
 
 CONFIG_OF = {"c1": "configs[0]", "c2": "configs[1]", "c3": "configs[2]", "c4": "configs[3]",
              "c5": "configs[4]"}
@@ -72,6 +86,131 @@ def cpu_baseline(inp, target_s=12.0):
                       f"{t:.2f} s)"}
 
 
+def one_thread_oracle(names=("c1", "c2")):
+    """The oracle on ONE host thread over the whole of the small workloads, for scale."""
+    import numpy as np
+    from oracle import gh_oracle as O
+    from paper_2501_11779_amd import workloads as W
+
+    out = {}
+    threads = O.num_threads()
+    O.set_num_threads(1)
+    try:
+        for name in names:
+            w = W.WORKLOADS[name]
+            inp = W.make_inputs(w, "cpu")
+            kc, vc = W.bits(inp["k_cache"]), W.bits(inp["v_cache"])
+            p = O.make_problem(w.batch, w.n_q_heads, w.n_kv_heads, w.head_dim, W.DTYPE_CODE[w.dtype],
+                               inp["n_slots"], inp["capacity"], inp["scale"], inp["strides"])
+            sid, pos = inp["slots"].astype(np.int32), inp["lengths"].astype(np.int32)
+            t0 = time.perf_counter()
+            O.kv_append(p, kc, vc, W.bits(inp["k_new"]), W.bits(inp["v_new"]), sid, pos)
+            O.decode_attention(p, W.bits(inp["q"]), kc, vc, sid, pos + 1)
+            t = time.perf_counter() - t0
+            out[name] = {"value": w.batch / t, "unit": "sequence-steps/s", "cores": 1,
+                         "sample": f"all {w.batch} sequences, {t:.2f} s"}
+    finally:
+        O.set_num_threads(threads)
+    return out
+
+
+def time_default_step(name, steps, warmup):
+    """Append + attention + merge of workload `name` in the library's default launch, timed like
+    the headline workload (wall clock for the step, HIP events on the launch stream per kernel)."""
+    import numpy as np
+    import torch
+    from paper_2501_11779_amd import binding as G
+    from paper_2501_11779_amd import workloads as W
+
+    w = W.WORKLOADS[name]
+    inp = W.make_inputs(w, "cuda")
+    p = G.problem_from_inputs(inp)
+    ws = G.alloc_workspace(p)
+    out = torch.empty((w.batch, w.n_q_heads, w.head_dim), device="cuda", dtype=torch.float32)
+    ctx = inp["lengths"].astype(np.int64) + 1
+    attn_bytes = W.attention_bytes(w, ctx)
+
+    def step(ev=None):
+        G.check(G.gh_kv_append(p, inp["k_cache"], inp["v_cache"], inp["k_new"], inp["v_new"],
+                               inp["slot_id"], inp["pos"], None))
+        if ev is not None:
+            ev[0].record()
+        G.check(G.gh_decode_attention(p, inp["q"], inp["k_cache"], inp["v_cache"], inp["slot_id"],
+                                      inp["ctx_len"], ws))
+        if ev is not None:
+            ev[1].record()
+        G.check(G.gh_decode_reduce(p, ws, inp["ctx_len"], out))
+        if ev is not None:
+            ev[2].record()
+
+    for _ in range(warmup):
+        step()
+    evs = [[torch.cuda.Event(enable_timing=True) for _ in range(3)] for _ in range(steps)]
+    torch.cuda.synchronize()
+    t0 = time.perf_counter()
+    for i in range(steps):
+        step(evs[i])
+    torch.cuda.synchronize()
+    elapsed = time.perf_counter() - t0
+    attn_ms = np.array([e[0].elapsed_time(e[1]) for e in evs])
+    red_ms = np.array([e[1].elapsed_time(e[2]) for e in evs])
+    achieved = attn_bytes / (float(attn_ms.mean()) * 1e-3) / 1e9
+    traffic, _ = measured_traffic(name)
+    res = {"workload": f"{CONFIG_OF[name]}: B={w.batch}, H={w.n_q_heads}, H_kv={w.n_kv_heads}, "
+                       f"{w.dtype}, lengths={list(w.lengths)}, seed={w.seed}",
+           "steps": steps, "warmup": warmup, "ms_per_step": elapsed / steps * 1e3,
+           "sequence_steps_per_s": w.batch * steps / elapsed,
+           "attention_ms_mean": float(attn_ms.mean()), "attention_ms_median": float(np.median(attn_ms)),
+           "attention_ms_min": float(attn_ms.min()), "reduce_ms": float(red_ms.mean()),
+           "algorithmic_bytes_per_launch": attn_bytes, "attention_GBps": achieved,
+           "frac": achieved / HBM_PEAK_GBS, "traffic": traffic}
+    log(f"{name}: step {res['ms_per_step']:.4f} ms | attention mean {attn_ms.mean():.4f} median "
+        f"{np.median(attn_ms):.4f} min {attn_ms.min():.4f} ms = {achieved:.0f} GB/s = "
+        f"{res['frac'] * 100:.1f}% | reduce {red_ms.mean():.4f} ms")
+    del inp, ws, out
+    torch.cuda.empty_cache()
+    return res
+
+
+def ceiling(args):
+    """Rate of the streaming-read probe: 2048 waves (the attention kernel's grid) over 8 GiB."""
+    import torch
+    from paper_2501_11779_amd import binding as G
+
+    n_waves, nbytes = 2048, 8 << 30
+    src = torch.ones(nbytes // 4, dtype=torch.int32, device="cuda")
+    rec = torch.empty(n_waves * 1024, dtype=torch.int32, device="cuda")
+    sink = torch.zeros(1, dtype=torch.int32, device="cuda")
+    tiles_per_wave = nbytes // (n_waves * 16384)
+    rows = {}
+    cases = [("reads only", 0, 0)]
+    for every in (64, 16):           # a 4 KiB store per 1 MiB / 256 KiB read by a wave
+        for name, pol in (("plain", G.GH_PROBE_STORE_PLAIN), ("non-temporal", G.GH_PROBE_STORE_NT),
+                          ("write-through", G.GH_PROBE_STORE_WRITE_THROUGH)):
+            cases.append((f"4 KiB {name} store per {every} tiles", every, pol))
+    for label, every, pol in cases:
+        def run():
+            G.check(G.gh_probe_stream_read(src, nbytes, n_waves, every, pol, rec, sink))
+        for _ in range(args.warmup):
+            run()
+        ev = [torch.cuda.Event(enable_timing=True) for _ in range(2)]
+        torch.cuda.synchronize()
+        ev[0].record()
+        for _ in range(args.steps):
+            run()
+        ev[1].record()
+        torch.cuda.synchronize()
+        ms = ev[0].elapsed_time(ev[1]) / args.steps
+        rows[label] = {"ms": ms, "GBps": nbytes / ms / 1e6}
+        log(f"stream probe, {label}: {ms:.4f} ms, {rows[label]['GBps']:.0f} GB/s = "
+            f"{rows[label]['GBps'] / HBM_PEAK_GBS * 100:.1f}% of {HBM_PEAK_GBS:.0f}")
+    print(json.dumps({"metric": "streaming-read probe (measurement aid, not the hot path)",
+                      "value": rows["reads only"]["GBps"], "unit": "GB/s", "n_gpus": 1,
+                      "steps": args.steps, "warmup": args.warmup,
+                      "config": {"workload": f"8 GiB read once by {n_waves} waves, {tiles_per_wave} "
+                                             f"tiles of 16 KiB each", "cases": rows}}), flush=True)
+
+
 def main():
     ap = argparse.ArgumentParser()
     ap.add_argument("--gpus", type=int, default=1)
@@ -115,6 +254,14 @@ def main():
                          "rocprofv3 FETCH_SIZE / WRITE_SIZE readings are scaled by")
     ap.add_argument("--traffic-bytes", type=float, default=None,
                     help="HBM bytes per attention launch from rocprofv3 counters, if measured")
+    ap.add_argument("--ceiling", action="store_true",
+                    help="measurement aid instead of the step: the streaming-read probe of "
+                         "include/gh_probe.h (pure reads in the attention kernel's access shape, "
+                         "alone and with record-sized stores in each store policy)")
+    ap.add_argument("--no-other-workloads", action="store_true",
+                    help="skip the short timings of the other full-size workloads that the default "
+                         "run adds under config.other_workloads")
+    ap.add_argument("--other-steps", type=int, default=30)
     args = ap.parse_args()
     if args.gpus != 1:
         sys.exit("bench.py: this build runs on one GPU only (the path shards by sequence, with no "
@@ -133,6 +280,8 @@ def main():
     log(f"device: {props.name} CUs={props.multi_processor_count} "
         f"mem={props.total_memory / 2**30:.0f} GiB host_cpus={os.cpu_count()}")
 
+    if args.ceiling:
+        return ceiling(args)
     w = W.WORKLOADS[args.workload]
     if args.batch or args.const_len:
         import dataclasses
@@ -264,6 +413,11 @@ def main():
         graph_ms = (time.perf_counter() - t0) / args.steps * 1e3
         log(f"HIP graph replay: {graph_ms:.4f} ms per step (eager {ms_per_step:.4f})")
 
+    plain = args.kernel == "auto" and not (
+        args.chunk_rows or args.batch or args.const_len or args.capacity or args.paged or args.mixed
+        or args.prefill or args.group or args.out16 or args.early)
+    traffic, traffic_source = (args.traffic_bytes, "command line") if args.traffic_bytes is not None \
+        else measured_traffic(w.name) if plain else (None, None)
     result = {
         "metric": "decode-attention sequence-steps/sec (achieved HBM GB/s and % of peak under roofline)",
         "value": w.batch * args.steps / elapsed,
@@ -280,21 +434,32 @@ def main():
                            + ("gh_decode_reduce_native" if args.out16 else "gh_decode_reduce"),
                    "paged_slots": paged_info, "hip_graph_ms_per_step": graph_ms,
                    "step_algorithmic_bytes": step_bytes,
-                   "step_GBps": step_bytes / (elapsed / args.steps) / 1e9},
+                   "step_GBps": step_bytes / (elapsed / args.steps) / 1e9,
+                   "attention_ms_mean": float(attn_ms.mean()),
+                   "attention_ms_median": float(np.median(attn_ms)),
+                   "attention_ms_min": float(attn_ms.min()),
+                   "reduce_ms": float(red_ms.mean())},
         "roofline": {"bound": "hbm", "kernel": "gh_decode_attention",
                      "achieved": achieved, "peak": HBM_PEAK_GBS, "unit": "GB/s",
                      "frac": achieved / HBM_PEAK_GBS,
-                     "traffic": args.traffic_bytes if args.traffic_bytes is not None else (
-                         MEASURED_TRAFFIC_BYTES.get(w.name)
-                         if args.kernel == "auto" and not (args.chunk_rows or args.batch or args.const_len or args.capacity or args.paged
-                                                      or args.mixed or args.prefill or args.group or args.out16 or args.early)
-                         else None),
+                     "traffic": traffic, "traffic_source": traffic_source,
                      "algorithmic_bytes_per_launch": attn_bytes,
                      "avg_launch_ms": float(attn_ms.mean())},
     }
     if not args.no_cpu_baseline:
         result["cpu_baseline"] = cpu if cpu is not None else cpu_baseline(inp)
         log(f"cpu_baseline: {result['cpu_baseline']}")
+        result["cpu_baseline"]["one_thread"] = one_thread_oracle()
+        log(f"one-thread oracle: {result['cpu_baseline']['one_thread']}")
+    if plain and w.name == "c4" and not args.no_other_workloads:
+        # the other full-size workloads of the target, each for a few steps in the same launch
+        # configuration, so that one run's record covers them all
+        del inp, ws, out
+        if pool is not None:
+            pool.close()
+        torch.cuda.empty_cache()
+        result["config"]["other_workloads"] = {
+            name: time_default_step(name, args.other_steps, 10) for name in ("c3", "c5", "c2", "c1")}
     print(json.dumps(result), flush=True)
 
 

@@ -26,6 +26,7 @@ EXPORTS = ("gh_status_string", "gh_decode_chunk_rows", "gh_decode_num_chunks",
            "gh_decode_reduce_native", "gh_decode_split_plan", "gh_decode_attention_out",
            "gh_decode_attention_static")
 GH_OUT_F32, GH_OUT_NATIVE = 0, 1
+GH_PROBE_STORE_PLAIN, GH_PROBE_STORE_NT, GH_PROBE_STORE_WRITE_THROUGH = 0, 1, 2
 POOL_EXPORTS = ("gh_slot_pool_create", "gh_slot_pool_destroy", "gh_slot_pool_k", "gh_slot_pool_v",
                 "gh_slot_pool_strides", "gh_slot_pool_reserve", "gh_slot_pool_release",
                 "gh_slot_pool_mapped_rows", "gh_slot_pool_get_stats", "gh_slot_pool_blocks")
@@ -108,6 +109,8 @@ def lib():
         L.gh_decode_reduce.argtypes = [P, V, V, V, V]
         L.gh_decode_reduce_native.restype = C.c_int32
         L.gh_decode_reduce_native.argtypes = [P, V, V, V, V]
+        L.gh_probe_stream_read.restype = C.c_int32
+        L.gh_probe_stream_read.argtypes = [V, C.c_size_t, C.c_int32, C.c_int32, C.c_int32, V, V, V]
         I32P = C.POINTER(C.c_int32)
         I64P = C.POINTER(C.c_int64)
         L.gh_slot_pool_create.restype = C.c_int32
@@ -218,6 +221,14 @@ def gh_decode_split_plan(p):
     out = gh_split_plan()
     check(lib().gh_decode_split_plan(C.byref(p), C.byref(out)))
     return out
+
+
+def gh_probe_stream_read(src, nbytes, n_waves, store_every, store_policy, rec, sink, stream=None):
+    """Measurement aid of include/gh_probe.h (stream = 0 is accepted without a GPU for the host-side
+    argument checks)."""
+    return lib().gh_probe_stream_read(_ptr(src), int(nbytes), int(n_waves), int(store_every),
+                                      int(store_policy), _ptr(rec), _ptr(sink),
+                                      0 if stream == 0 else _stream(stream))
 
 
 def check(status):

@@ -17,7 +17,7 @@ FLAGS = [
 
 def build_lib(verbose: bool = False, extra=()) -> str:
     cmd = [HIPCC, *FLAGS, *extra, "-I", os.path.join(ROOT, "include"), "-I", CSRC,
-           os.path.join(CSRC, "gh_tier2.hip"), os.path.join(CSRC, "gh_slot_pool.hip"), os.path.join(CSRC, "gh_sim.hip"), "-o", LIB]
+           os.path.join(CSRC, "gh_tier2.hip"), os.path.join(CSRC, "gh_slot_pool.hip"), os.path.join(CSRC, "gh_sim.hip"), os.path.join(CSRC, "gh_probe.hip"), "-o", LIB]
     if verbose:
         print(" ".join(cmd))
     res = subprocess.run(cmd, stdout=subprocess.PIPE, stderr=subprocess.STDOUT, text=True)

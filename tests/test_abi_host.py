@@ -54,6 +54,18 @@ def test_slot_pool_symbols_are_exported_and_arguments_checked_without_a_gpu():
     assert L.gh_slot_pool_reserve(None, None, None, 0) == G.GH_ERR_NULL
 
 
+def test_probe_symbol_is_exported_and_arguments_checked_without_a_gpu():
+    assert _declared_functions("gh_probe.h") == ["gh_probe_stream_read"]
+    a, MiB = 1 << 20, 1 << 20
+    f = lambda *x: G.gh_probe_stream_read(*x, stream=0)
+    assert f(None, 64 * MiB, 2048, 0, 0, None, a) == G.GH_ERR_NULL
+    assert f(a, 64 * MiB, 2048, 4, 0, None, a) == G.GH_ERR_NULL               # stores need `rec`
+    assert f(a, 64 * MiB, 2046, 0, 0, None, a) == G.GH_ERR_SHAPE              # waves in fours
+    assert f(a, 64 * MiB + 4096, 2048, 0, 0, None, a) == G.GH_ERR_SHAPE       # whole tile pairs per wave
+    assert f(a + 8, 64 * MiB, 2048, 0, 0, None, a) == G.GH_ERR_UNSUPPORTED
+    assert f(a, 64 * MiB, 2048, 4, 9, a, a) == G.GH_ERR_UNSUPPORTED
+
+
 def test_status_strings():
     for st in range(0, -8, -1):
         assert G.gh_status_string(st) not in ("", "unknown status")
@@ -257,7 +269,7 @@ def test_public_headers_are_plain_c(tmp_path):
     import subprocess
     inc = os.path.join(ROOT, "include")
     headers = sorted(f for f in os.listdir(inc) if f.endswith(".h"))
-    assert headers == ["gh_sim.h", "gh_slot_pool.h", "gh_tier2.h"]
+    assert headers == ["gh_probe.h", "gh_sim.h", "gh_slot_pool.h", "gh_tier2.h"]
     for h in headers:
         src = tmp_path / (h[:-2] + "_only.c")
         src.write_text(f'#include "{h}"\nint main(void) {{ return 0; }}\n')
