@@ -49,10 +49,11 @@
  *     lets the tokens of a prefill chunk share one pass over their slot.  Batch
  *     rows kT .. kT+T-1 form group k and address one slot; each row keeps its
  *     own ctx_len (and q, position, output row).  gh_decode_attention then
- *     streams the slot's K/V rows once per 32 of the T*G query heads a group
- *     has per kv head -- they fill the head columns of two matrix-core tiles
- *     fed from one stream, each column masked at its own token's length --
- *     instead of once per row.  A
+ *     fetches the slot's K/V rows from memory once per 128 of the T*G query
+ *     heads a group has per kv head -- a wave carries 32 of them as the head
+ *     columns of two matrix-core tiles fed from one stream of rows, up to four
+ *     waves of a workgroup walk the same rows together, and each column is
+ *     masked at its own token's length -- instead of once per row.  A
  *     row with ctx_len 0, a bad slot id, or a slot other than that of the
  *     group's first live row gets no rows (output zero), so short groups are
  *     padded with ctx_len = 0 rows and a decode entry is a group with one live
@@ -153,7 +154,11 @@ const char* gh_status_string(int32_t status);
  * the output (gh_decode_attention_out).
  * For record c of (sequence b, head h), over the rows r it covers and with
  * t_r = scale * log2(e) * (q . K_r):
- *   m = max_r t_r,  l = sum_r 2^(t_r - m),  o[:] = sum_r 2^(t_r - m) * V_r[:]
+ *   l = sum_r 2^(t_r - m),  o[:] = sum_r 2^(t_r - m) * V_r[:]
+ * where m is the exponent the sums are scaled by: max_r t_r - 8 <= m <= max_r t_r
+ * (the matrix-core kernel lets it trail the running maximum by up to 2^8 to save
+ * rescaling; any m in that range describes the same partial result, and the
+ * merge only uses m as that common factor).
  * A record in use that covers no rows has m = -inf, l = 0, unspecified o.
  */
 int32_t gh_decode_chunk_rows(const gh_problem* p);
@@ -163,9 +168,9 @@ size_t gh_decode_workspace_bytes(const gh_problem* p);
 /*
  * The numbers behind the balanced split, for callers and tests that want to
  * reason about it (host function).  Every strip -- (group, kv head, set of
- * passes_per_strip passes of 16 head columns) -- counts ceil(rows / 32) tiles of
+ * passes_per_strip * waves_per_worker passes of 16 head columns) -- counts ceil(rows / 32) tiles of
  * 32 rows, at least one; the strips are laid end to end in batch order, kv head
- * next, pass set fastest; wave w of n_workers takes tiles [w*share, (w+1)*share)
+ * next, pass set fastest; worker w of n_workers takes tiles [w*share, (w+1)*share)
  * with share = max(ceil(total / n_workers), min_share); the record a wave
  * writes for a strip has index w - floor(first tile of the strip / share).
  * min_share is what keeps that index below gh_decode_num_chunks for every
@@ -173,11 +178,14 @@ size_t gh_decode_workspace_bytes(const gh_problem* p);
  */
 typedef struct {
   int32_t balanced;           /* 0: fixed split, the other fields are 0          */
-  int32_t n_workers;          /* waves                                           */
-  int32_t min_share;          /* least tiles per wave                            */
+  int32_t n_workers;          /* workers (waves, or sets of waves_per_worker)    */
+  int32_t min_share;          /* least tiles per worker                          */
   int32_t passes_per_strip;   /* 1 or 2                                          */
   int32_t strips_per_kv_head; /* pass sets per (group, kv head)                  */
   int32_t n_chunks;           /* = gh_decode_num_chunks                          */
+  int32_t waves_per_worker;   /* 1, 2 or 4: the waves of a worker walk the same
+                                 tiles, each with its own passes_per_strip passes
+                                 (a strip then stands for their product of passes) */
 } gh_split_plan;
 int32_t gh_decode_split_plan(const gh_problem* p, gh_split_plan* out);
 

@@ -93,29 +93,45 @@ __device__ __forceinline__ u32x4 lower_from_rotated(const u32x4& keep, const u32
   return r;
 }
 
-__device__ __forceinline__ void load_tile(TileRegs& t, const uint16_t* kbase, const uint16_t* vbase,
-                                          const AttnArgs& a, int tile_row0, int last, int hn, int c) {
+// What a lane contributes to the addresses of a tile's loads: its row inside the tile (plus a
+// per-register constant) and its byte column, for K and for V.
+struct LaneGeom {
+  int krow, vrow;          // K: register (T, ab) holds in-tile row krow + 16 T + 2 ab;  V: register e holds
+                           // in-tile row vrow + 16 (e >> 2) + 4 (e & 3)
+  uint32_t kcol, vcol;     // byte offsets inside the row (K: first 128-byte half)
+};
+__device__ __forceinline__ LaneGeom lane_geom(int hn, int c) {
+  // K row rho(T, m) = 16 T + 4 (m & 3) + (m >> 2) with m = (hn & 7) + 8 ab
+  return LaneGeom{4 * (hn & 3) + ((hn & 7) >> 2), c, (uint32_t)(64 * (hn >> 3) + 16 * c),
+                  (uint32_t)(16 * hn)};
+}
+
+// Loads one tile.  kt / vt: address of the tile's first row in the K and the V strip, the same for
+// every lane (a tile is 32-row aligned and never straddles two blocks of a blocked layout), so an
+// address is that scalar plus a 32-bit lane offset: two vector instructions per address.
+// `rows` (>= 1): how many of the tile's 32 rows exist; the others load the last existing row.
+template <bool NT>
+__device__ __forceinline__ void load_tile(TileRegs& t, const char* kt, const char* vt,
+                                          uint32_t row_bytes, int rows, const LaneGeom& lg) {
+  const int top = rows - 1;
   // K: one load covers 8 rows x 128 bytes (whole cache lines): lanes hn < 8 take the first
   // 64 bytes of the half-row, lanes hn >= 8 the second 64 bytes of the same row.
 #pragma unroll
   for (int T = 0; T < 2; ++T) {
 #pragma unroll
     for (int ab = 0; ab < 2; ++ab) {
-      const int mrow = (hn & 7) + 8 * ab;                          // row index within the sub-tile
-      int row = tile_row0 + 16 * T + 4 * (mrow & 3) + (mrow >> 2);  // rho(T, mrow)
-      row = row < last ? row : last;
-      const uint16_t* kp = kbase + row_offset(row, a.row_stride, a.block_stride, a.block_shift, a.block_mask) +
-                           32 * (hn >> 3) + 8 * c;
+      int r = lg.krow + 16 * T + 2 * ab;
+      r = r < top ? r : top;
+      const uint32_t off = __umul24((uint32_t)r, row_bytes) + lg.kcol;
 #pragma unroll
-      for (int half = 0; half < 2; ++half) t.k[T][half][ab] = stream_load(kp + 64 * half);
+      for (int half = 0; half < 2; ++half) t.k[T][half][ab] = stream_load_at<NT>(kt, off + 128 * half);
     }
   }
 #pragma unroll
   for (int e = 0; e < 8; ++e) {
-    int row = tile_row0 + 16 * (e >> 2) + 4 * (e & 3) + c;
-    row = row < last ? row : last;
-    t.v[e] = stream_load(vbase + row_offset(row, a.row_stride, a.block_stride, a.block_shift, a.block_mask) +
-                         8 * hn);
+    int r = lg.vrow + 16 * (e >> 2) + 4 * (e & 3);
+    r = r < top ? r : top;
+    t.v[e] = stream_load_at<NT>(vt, __umul24((uint32_t)r, row_bytes) + lg.vcol);
   }
 }
 
@@ -151,19 +167,34 @@ __device__ __forceinline__ void process_tile(const TileRegs& t, const u32x4 (&qo
   for (int i = 0; i < P; ++i) {
     float tv[8];
     float mx = kNegInf;
+    // rows at or beyond the column's limit are masked (select, not multiply: what lies there may
+    // be anything); a tile that every column of the wave attends in full skips the selects
+    if (__all(tile_row0 + 32 <= lim[i])) {
 #pragma unroll
-    for (int e = 0; e < 8; ++e) {
-      const int row = tile_row0 + 16 * (e >> 2) + 4 * (e & 3) + c;
-      tv[e] = row < lim[i] ? s[i][e >> 2][e & 3] * scale_log2e : kNegInf;
-      mx = fmaxf(mx, tv[e]);
+      for (int e = 0; e < 8; ++e) {
+        tv[e] = s[i][e >> 2][e & 3] * scale_log2e;
+        mx = fmaxf(mx, tv[e]);
+      }
+    } else {
+#pragma unroll
+      for (int e = 0; e < 8; ++e) {
+        const int row = tile_row0 + 16 * (e >> 2) + 4 * (e & 3) + c;
+        tv[e] = row < lim[i] ? s[i][e >> 2][e & 3] * scale_log2e : kNegInf;
+        mx = fmaxf(mx, tv[e]);
+      }
     }
-    mx = fmaxf(mx, xor16(mx));
-    mx = fmaxf(mx, xor32(mx));
-    const float mn = fmaxf(m[i], mx);
+    mx = rows_max(mx);
+    // m is the exponent the column's running sums are scaled by.  It follows the running maximum
+    // lazily: the sums are rescaled only when the maximum has grown by more than kLazyExponent
+    // since the last time, so that the weights 2^(t - m) stay below 2^kLazyExponent instead of
+    // below 1 -- the same relative precision, and after the first tiles of a strip hardly any
+    // tile pays for a rescale.  (m = -inf: no row seen yet; then any row moves it.)
+    const bool moved = mx > m[i] + kLazyExponent;
+    const float mn = moved ? mx : m[i];
     // a column that has seen no row yet keeps m = -inf; subtract 0 then, so that every exponent
     // below is -inf (weight 0) rather than inf - inf
     const float ref = mn == kNegInf ? 0.f : mn;
-    const float alpha = fast_exp2(m[i] - ref);
+    const float alpha = moved ? fast_exp2(m[i] - ref) : 1.f;
     m[i] = mn;
     float sum = 0.f;
     float lo[8];
@@ -183,7 +214,7 @@ __device__ __forceinline__ void process_tile(const TileRegs& t, const u32x4 (&qo
       p_hi[i][w] = hi;
       p_lo[i][w] = pack2<BF16>(lo[2 * w], lo[2 * w + 1]);
     }
-    if (__any(alpha != 1.f)) {
+    if (__any(moved)) {
 #pragma unroll
       for (int tcol = 0; tcol < 8; ++tcol) acc[i][tcol] *= alpha;
     }
@@ -287,8 +318,7 @@ __device__ __forceinline__ void whole_line_chunks(f32x4 (&x)[8]) {
 __device__ __forceinline__ void store_record(const AttnArgs& a, int b, int g, int pass, int nh,
                                              int slot, const f32x4 (&acc)[8], float m, float l,
                                              int hn, int c) {
-  l += xor16(l);                       // the four lanes of a head share m; add their partial sums
-  l += xor32(l);
+  l = rows_sum(l);                     // the four lanes of a head share m; add their partial sums
   f32x4 x[8];                          // chunk q = columns 32c + 4q .. 32c + 4q + 3
 #pragma unroll
   for (int i = 0; i < 4; ++i) {
@@ -338,8 +368,7 @@ template <bool BF16>
 __device__ __forceinline__ void store_final(const AttnArgs& a, int b, int g, int pass, int nh,
                                             const f32x4 (&acc)[8], float l, int hn, int c) {
   typedef uint32_t u32x2 __attribute__((ext_vector_type(2)));
-  l += xor16(l);
-  l += xor32(l);
+  l = rows_sum(l);
   f32x4 x[8];
 #pragma unroll
   for (int i = 0; i < 4; ++i) {
@@ -400,19 +429,26 @@ __device__ __forceinline__ void run_strip(const AttnArgs& a, int b, int g, int p
   float m[1] = {kNegInf}, l[1] = {0.f};
   const int lim[1] = {r1};
 
-  const uint16_t* kbase = a.k_cache + strip;
-  const uint16_t* vbase = a.v_cache + strip;
+  const LaneGeom lg = lane_geom(hn, c);
+  const uint32_t row_bytes = (uint32_t)a.row_stride * 2u;
   const int last = r1 - 1;
+  // tile at row0 (a multiple of 32); past the end, the tile that holds the last row once more
+  auto issue = [&](TileRegs& t, int row0) {
+    row0 = row0 <= last ? row0 : last & ~31;
+    const int64_t at = strip + row_offset(row0, a.row_stride, a.block_stride, a.block_shift, a.block_mask);
+    load_tile<true>(t, reinterpret_cast<const char*>(a.k_cache + at),
+                    reinterpret_cast<const char*>(a.v_cache + at), row_bytes, r1 - row0, lg);
+  };
 
   // Two register tiles in flight.  The loads are issued unconditionally (rows past the end are
   // clamped to the last row, whose lines are already in cache) so that the number of outstanding
   // loads is known at every wait and a tile's arithmetic overlaps the next tile's loads.
   TileRegs ta, tb;
-  load_tile(ta, kbase, vbase, a, r0, last, hn, c);
+  issue(ta, r0);
   for (int row0 = r0; row0 < r1; row0 += 64) {
-    load_tile(tb, kbase, vbase, a, row0 + 32, last, hn, c);
+    issue(tb, row0 + 32);
     process_tile<BF16, 1>(ta, qop, acc, m, l, a.scale_log2e, row0, lim, c);
-    load_tile(ta, kbase, vbase, a, row0 + 64, last, hn, c);
+    issue(ta, row0 + 64);
     if (row0 + 32 < r1) process_tile<BF16, 1>(tb, qop, acc, m, l, a.scale_log2e, row0 + 32, lim, c);
   }
 
@@ -479,10 +515,12 @@ struct TileCursor {
 // P = passes of 16 head columns a wave carries through a strip at once (own Q operand, running
 // state and accumulators per pass, one stream of tiles for all): 1 for decode, 2 for token groups
 // with more than 16 head columns, at one wave per SIMD instead of two.
-template <bool BF16, bool GROUPED, int P>
+// SHARED: the waves of a workgroup walk the same tiles in sets of a.share (> 1), see below.
+template <bool BF16, bool GROUPED, int P, bool SHARED>
 __global__ __launch_bounds__(256, P == 1 ? 2 : 1) void attn_mfma_balanced_kernel(const AttnArgs a) {
+  constexpr int kThreads = 256;
   extern __shared__ uint32_t lds[];
-  __shared__ uint32_t part[256];
+  __shared__ uint32_t part[kThreads];
   const int tid = threadIdx.x;
   const int B = a.batch;
   uint32_t* cum = lds;                                        // [B + 1]
@@ -490,7 +528,7 @@ __global__ __launch_bounds__(256, P == 1 ? 2 : 1) void attn_mfma_balanced_kernel
   int* slots = rows + B;                                      // [B]
   const uint32_t spb = (uint32_t)(a.n_kv_heads * a.n_pass);   // strips per sequence
 
-  for (int b = tid; b < B; b += 256) {
+  for (int b = tid; b < B; b += kThreads) {
     int slot = 0, n = 0;
     for (int t = 0; t < a.tokens; ++t) {
       const int st = a.slot_id[(int64_t)b * a.tokens + t];
@@ -506,13 +544,13 @@ __global__ __launch_bounds__(256, P == 1 ? 2 : 1) void attn_mfma_balanced_kernel
   }
   if (tid == 0) cum[0] = 0;
   __syncthreads();
-  const int per = (B + 255) / 256;
+  const int per = (B + kThreads - 1) / kThreads;
   const int lo = tid * per, hi = lo + per < B ? lo + per : B;
   uint32_t sum = 0;
   for (int b = lo; b < hi; ++b) sum += cum[b + 1];
   part[tid] = sum;
   __syncthreads();
-  for (int off = 1; off < 256; off <<= 1) {
+  for (int off = 1; off < kThreads; off <<= 1) {
     const uint32_t add = tid >= off ? part[tid - off] : 0u;
     __syncthreads();
     part[tid] += add;
@@ -530,7 +568,14 @@ __global__ __launch_bounds__(256, P == 1 ? 2 : 1) void attn_mfma_balanced_kernel
   const uint32_t total = uni(cum[B]);
   const int lane = tid & 63;
   const int hn = lane & 15, c = lane >> 4;
-  const uint32_t gw = blockIdx.x * 4 + uni(tid >> 6);          // global wave number
+  // Worker = `share` consecutive waves of a workgroup (1, 2 or 4) that walk the same tiles, each
+  // with its own passes; gw numbers the workers.  The waves of a worker run the same instruction
+  // stream on the same addresses at nearly the same time, so the tile is fetched from memory once
+  // and the other waves' loads are served by the cache.
+  const uint32_t wave = uni(tid >> 6);
+  const uint32_t n_share = SHARED ? (uint32_t)a.share : 1u;
+  const uint32_t gw = (blockIdx.x * 4 + wave) / n_share;
+  const int wsub = (int)(wave % n_share) * P;                  // first pass of this wave in a strip's set
   uint32_t share = (total + a.n_workers - 1) / a.n_workers;    // tiles per wave
   share = share > (uint32_t)a.min_share ? share : (uint32_t)a.min_share;
   const uint32_t t0 = gw * share;
@@ -558,7 +603,7 @@ __global__ __launch_bounds__(256, P == 1 ? 2 : 1) void attn_mfma_balanced_kernel
   // real (0 for a pass beyond the group's columns; the first pass of a strip always has some).
   auto pass_of = [&](uint32_t sib, int& g, int& pass0, int (&nh)[P]) {
     g = (int)(sib / (uint32_t)a.n_pass);
-    pass0 = (int)(sib % (uint32_t)a.n_pass) * P;
+    pass0 = (int)(sib % (uint32_t)a.n_pass) * (P * (int)n_share) + wsub;
 #pragma unroll
     for (int i = 0; i < P; ++i) {
       const int left = a.group - (pass0 + i) * a.heads_per_pass;
@@ -585,14 +630,27 @@ __global__ __launch_bounds__(256, P == 1 ? 2 : 1) void attn_mfma_balanced_kernel
       return x.n;
     }
   };
+  const LaneGeom lg = lane_geom(hn, c);
+  const uint32_t row_bytes = (uint32_t)a.row_stride * 2u;
   auto issue = [&](TileRegs& regs, const TileCursor& cu) {
     const int g = (int)(cu.sib / (uint32_t)a.n_pass);
-    const int64_t strip = (int64_t)cu.slot * a.slot_stride + (int64_t)g * a.head_stride;
+    const int row0 = (int)cu.lt * 32;
     // A strip without rows reads the first 256 bytes of q instead: the loads stay unconditional,
     // and no cache address is touched that the caller did not declare attended (a paged cache
     // may have nothing mapped there).
-    load_tile(regs, cu.n > 0 ? a.k_cache + strip : a.q, cu.n > 0 ? a.v_cache + strip : a.q,
-              a, (int)cu.lt * 32, cu.n > 0 ? cu.n - 1 : 0, hn, c);
+    const char* kt = reinterpret_cast<const char*>(a.q);
+    const char* vt = kt;
+    int rows = 1;
+    if (cu.n > 0) {
+      const int64_t at = (int64_t)cu.slot * a.slot_stride + (int64_t)g * a.head_stride +
+                         row_offset(row0, a.row_stride, a.block_stride, a.block_shift, a.block_mask);
+      kt = reinterpret_cast<const char*>(a.k_cache + at);
+      vt = reinterpret_cast<const char*>(a.v_cache + at);
+      rows = cu.n - row0;
+    }
+    // (a wave of its own reads every row once: keep the stream out of the caches' way; when several
+    // waves ask for the same rows, let the cache keep them)
+    load_tile<!SHARED>(regs, kt, vt, row_bytes, rows, lg);
   };
 
   // cursor of the tile being computed; start: largest b with cum[b] <= t0
@@ -657,7 +715,12 @@ __global__ __launch_bounds__(256, P == 1 ? 2 : 1) void attn_mfma_balanced_kernel
   next_strip(qs);
 #pragma unroll
   for (int i = 0; i < P; ++i) qnext_nh[i] = 0;
-  if (qs.t < t_end) {
+  // The Q rows of the following strip are fetched a whole strip ahead -- by a wave that carries one
+  // pass.  With two passes the registers that would hold them are worth more than the stall: the
+  // compiler parks what does not fit in the accumulator registers and moves it back and forth in
+  // every tile; there the rows are fetched when the strip opens (one memory round trip per strip).
+  constexpr bool kPrefetchQ = P == 1;
+  if (kPrefetchQ && qs.t < t_end) {
     pass_of(qs.sib, qg, qpass0, qnext_nh);
     fetch(qs, qs.b, qg, qpass0, qnext_nh);
     lnext_slot = qs.slot;
@@ -708,6 +771,12 @@ __global__ __launch_bounds__(256, P == 1 ? 2 : 1) void attn_mfma_balanced_kernel
           m[i] = kNegInf;
           l[i] = 0.f;
         }
+        if constexpr (!kPrefetchQ) {
+          pass_of(qs.sib, g, pass0, nh);                       // qs: the strip that opens
+          fetch(qs, qs.b, g, pass0, nh);
+          take(nh, qs.slot);
+          next_strip(qs);
+        } else {
         take(qnext_nh, lnext_slot);
         g = qg;
         pass0 = qpass0;
@@ -731,22 +800,27 @@ __global__ __launch_bounds__(256, P == 1 ? 2 : 1) void attn_mfma_balanced_kernel
           }
           lnext_slot = more ? qs.slot : cp.slot;
         }
+        }
       }
     }
   };
 
-  // Two register tiles.  Loads are issued unconditionally (past the end of the share the last
-  // position is loaded again, from cache) so that every wait count is exact.
+  // Two register tiles: one is in flight while the other is computed.  Loads are issued
+  // unconditionally (past the end of the share the last position is loaded again, from cache) so
+  // that every wait count is exact.  (A third tile in flight was measured for the two-pass
+  // instantiation, which has the registers for it: no change -- it is not waiting for memory.)
+  auto load_next = [&](TileRegs& regs) {
+    if (ld.t + 1 < t_end) advance(ld);
+    issue(regs, ld);
+  };
   TileRegs ta, tb;
   issue(ta, ld);
   while (true) {
-    if (ld.t + 1 < t_end) advance(ld);
-    issue(tb, ld);
+    load_next(tb);
     compute(ta);
     if (cp.t + 1 >= t_end) break;
     advance(cp);
-    if (ld.t + 1 < t_end) advance(ld);
-    issue(ta, ld);
+    load_next(ta);
     compute(tb);
     if (cp.t + 1 >= t_end) break;
     advance(cp);

@@ -32,7 +32,8 @@ struct AttnArgs {
   int32_t heads_per_pass, n_pass;                 // head sub-groups of one kv head
   int32_t n_items;                                // B * H_kv * n_pass * n_chunks (fixed split)
   int32_t batch;
-  int32_t n_workers, min_share;                   // balanced split: waves, least tiles per wave
+  int32_t n_workers, min_share;                   // balanced split: workers, least tiles per worker
+  int32_t share;                                  // balanced split: waves per worker (1, 2 or 4)
   float scale_log2e;                              // scale * log2(e)
   void* out;                                      // final results of heads one wave covers alone
   int32_t out_kind;                               // 0 none, 1 fp32, 2 binary16, 3 bfloat16
@@ -111,6 +112,16 @@ __device__ __forceinline__ u32x4_t stream_load(const uint16_t* p) {
   return __builtin_nontemporal_load(reinterpret_cast<const u32x4_t*>(p));
 }
 
+// The same from a wave-uniform base address plus a 32-bit lane offset in bytes.
+// NT = false: an ordinary cached load, for rows that other waves are about to ask for as well.
+template <bool NT>
+__device__ __forceinline__ u32x4_t stream_load_at(const char* base, uint32_t off) {
+  if constexpr (NT)
+    return __builtin_nontemporal_load(reinterpret_cast<const u32x4_t*>(base + off));
+  else
+    return *reinterpret_cast<const u32x4_t*>(base + off);
+}
+
 // 2^x on the transcendental unit; 2^(-inf) = 0.
 __device__ __forceinline__ float fast_exp2(float x) { return __builtin_amdgcn_exp2f(x); }
 
@@ -149,6 +160,30 @@ __device__ __forceinline__ float row16_sum(float x) {
   x += __int_as_float(v);
   return x;
 }
+
+// Maximum / sum over the four lanes hn, hn + 16, hn + 32, hn + 48 (one per 16-lane row), delivered
+// to all four.  The swap instructions trade whole rows between two registers in one vector
+// operation (no trip through the LDS crossbar): permlane16_swap exchanges the odd rows of its first
+// operand with the even rows of its second, permlane32_swap the upper half of the first with the
+// lower half of the second; fed the same value twice they return (x of the even row, x of the odd
+// row) resp. (x of the lower half, x of the upper half) in every lane.
+typedef uint32_t u32x2_t __attribute__((ext_vector_type(2)));
+__device__ __forceinline__ float rows_max(float x) {
+  u32x2_t r = __builtin_amdgcn_permlane16_swap(__float_as_uint(x), __float_as_uint(x), false, false);
+  x = fmaxf(__uint_as_float(r[0]), __uint_as_float(r[1]));
+  r = __builtin_amdgcn_permlane32_swap(__float_as_uint(x), __float_as_uint(x), false, false);
+  return fmaxf(__uint_as_float(r[0]), __uint_as_float(r[1]));
+}
+__device__ __forceinline__ float rows_sum(float x) {
+  u32x2_t r = __builtin_amdgcn_permlane16_swap(__float_as_uint(x), __float_as_uint(x), false, false);
+  x = __uint_as_float(r[0]) + __uint_as_float(r[1]);
+  r = __builtin_amdgcn_permlane32_swap(__float_as_uint(x), __float_as_uint(x), false, false);
+  return __uint_as_float(r[0]) + __uint_as_float(r[1]);
+}
+
+// How far a column's running maximum may outgrow the exponent its sums are scaled by before they
+// are rescaled (base-2 exponent: weights stay below 2^8).
+constexpr float kLazyExponent = 8.f;
 
 // Exchange with the lane 16 / 32 positions away (across the four 16-lane rows of a wave).
 __device__ __forceinline__ float xor16(float x) { return __shfl_xor(x, 16, 64); }

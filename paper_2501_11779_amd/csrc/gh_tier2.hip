@@ -58,6 +58,8 @@ int32_t check_problem(const gh_problem* p) {
     return GH_ERR_UNSUPPORTED;
   if (p->row_stride < p->head_dim || p->head_stride <= 0 || p->slot_stride <= 0) return GH_ERR_SHAPE;
   if (p->row_stride % 8 || p->head_stride % 8 || p->slot_stride % 8) return GH_ERR_UNSUPPORTED;
+  // the kernels form a row's byte offset inside a 32-row tile with 24-bit multiplies
+  if (p->row_stride >= (1 << 22)) return GH_ERR_UNSUPPORTED;
   if (p->max_ctx_len > p->slot_capacity) return GH_ERR_CAPACITY;
   if (p->chunk_rows < 0 || p->chunk_rows % kChunkQuantum != 0) return GH_ERR_SHAPE;
   if (p->block_rows < 0 || (p->block_rows > 0 && p->block_stride <= 0)) return GH_ERR_SHAPE;
@@ -123,6 +125,8 @@ struct Plan {
   int n_workers, min_share; // balanced split only
   int passes_per_strip;     // balanced split: passes a wave carries through a strip at once;
                             // n_pass then counts strips per (group, kv head)
+  int share;                // balanced split: waves per worker; the waves of a worker walk the same
+                            // tiles, each with its own passes_per_strip passes
 };
 
 constexpr int kBalancedWavesPerCU = 8;      // resident waves of the MFMA kernel per compute unit
@@ -135,12 +139,17 @@ Plan make_plan(const gh_problem* p) {
   pl.balanced = false;
   pl.n_workers = pl.min_share = 0;
   pl.passes_per_strip = 1;
+  pl.share = 1;
   const int groups = p->batch / tokens_per_group(p);
   // More than 16 head columns per kv head (a token group, or a head group above 16): two passes
   // share one stream of tiles, at one wave per SIMD (the second pass's operands and accumulators
   // take the other wave's registers).
   const int pps = pl.n_pass > 1 ? 2 : 1;
-  const int n_strip = (pl.n_pass + pps - 1) / pps;
+  // More than 32: up to four waves of a workgroup share one stream of tiles, so that K/V rows are
+  // read from memory once per 128 head columns.
+  const int sets = (pl.n_pass + pps - 1) / pps;
+  const int share = sets >= 3 ? 4 : sets;
+  const int n_strip = (sets + share - 1) / share;
   const int64_t strips = (int64_t)(groups > 0 ? groups : 1) * p->n_kv_heads * n_strip;
   const int64_t max_tiles = p->max_ctx_len > 0 ? (p->max_ctx_len + 31) / 32 : 1;
   if (pl.kernel == GH_KERNEL_MFMA && p->chunk_rows == 0 && groups <= kBalancedMaxBatch &&
@@ -150,7 +159,8 @@ Plan make_plan(const gh_problem* p) {
     pl.balanced = true;
     pl.passes_per_strip = pps;
     pl.n_pass = n_strip;
-    pl.n_workers = kComputeUnits * (pps == 1 ? kBalancedWavesPerCU : kBalancedWavesPerCU / 2);
+    pl.share = share;
+    pl.n_workers = kComputeUnits * (pps == 1 ? kBalancedWavesPerCU : kBalancedWavesPerCU / 2) / share;
     int64_t c = (4 * (int64_t)pl.n_workers + strips - 1) / strips + 1;
     if (c < 2) c = 2;
     if (c > kBalancedMaxRecords) c = kBalancedMaxRecords;
@@ -167,6 +177,26 @@ Plan make_plan(const gh_problem* p) {
 
 size_t workspace_floats(const gh_problem* p, const Plan& pl) {
   return (size_t)p->batch * p->n_q_heads * ((size_t)pl.n_chunks * (gh::kHeadDim + 2) + 1);
+}
+
+// Instantiations of the balanced kernel: dtype x (token groups) x (one pass per wave | two passes,
+// alone or with the workgroup's waves sharing a stream).
+template <bool BF16, bool GROUPED>
+void launch_balanced_as(const gh::AttnArgs& a, int passes, bool shared, size_t lds, hipStream_t s) {
+  const dim3 grid(a.n_workers * a.share / 4), block(256);
+  if (passes == 1)
+    hipLaunchKernelGGL((gh::attn_mfma_balanced_kernel<BF16, GROUPED, 1, false>), grid, block, lds, s, a);
+  else if (!shared)
+    hipLaunchKernelGGL((gh::attn_mfma_balanced_kernel<BF16, GROUPED, 2, false>), grid, block, lds, s, a);
+  else
+    hipLaunchKernelGGL((gh::attn_mfma_balanced_kernel<BF16, GROUPED, 2, true>), grid, block, lds, s, a);
+}
+void launch_balanced(const gh::AttnArgs& a, bool bf16, bool grouped, int passes, bool shared,
+                     size_t lds, hipStream_t s) {
+  if (bf16 && grouped) launch_balanced_as<true, true>(a, passes, shared, lds, s);
+  else if (bf16) launch_balanced_as<true, false>(a, passes, shared, lds, s);
+  else if (grouped) launch_balanced_as<false, true>(a, passes, shared, lds, s);
+  else launch_balanced_as<false, false>(a, passes, shared, lds, s);
 }
 
 template <bool BF16>
@@ -223,6 +253,7 @@ int32_t gh_decode_split_plan(const gh_problem* p, gh_split_plan* out) {
     out->min_share = pl.min_share;
     out->passes_per_strip = pl.passes_per_strip;
     out->strips_per_kv_head = pl.n_pass;
+    out->waves_per_worker = pl.share;
   }
   return GH_OK;
 }
@@ -320,6 +351,7 @@ int32_t launch_attention(const gh_problem* p, const void* q, const void* k_cache
   a.batch = p->batch / a.tokens;                 // groups
   a.n_workers = pl.n_workers;
   a.min_share = pl.min_share;
+  a.share = pl.share;
   a.scale_log2e = p->scale * 1.44269504088896340736f;
   a.out = out;
   a.out_kind = out_kind == 0 ? 0 : out_kind == 1 ? 1 : p->dtype == GH_F16 ? 2 : 3;
@@ -327,29 +359,8 @@ int32_t launch_attention(const gh_problem* p, const void* q, const void* k_cache
   hipStream_t s = static_cast<hipStream_t>(hip_stream);
   const bool bf16 = p->dtype == GH_BF16;
   if (pl.balanced) {
-    const dim3 grid(pl.n_workers / 4), block(256);
     const size_t lds = (size_t)(3 * a.batch + 1) * sizeof(uint32_t);
-    if (pl.passes_per_strip == 2 && a.tokens > 1) {
-      if (bf16)
-        hipLaunchKernelGGL((gh::attn_mfma_balanced_kernel<true, true, 2>), grid, block, lds, s, a);
-      else
-        hipLaunchKernelGGL((gh::attn_mfma_balanced_kernel<false, true, 2>), grid, block, lds, s, a);
-    } else if (pl.passes_per_strip == 2) {
-      if (bf16)
-        hipLaunchKernelGGL((gh::attn_mfma_balanced_kernel<true, false, 2>), grid, block, lds, s, a);
-      else
-        hipLaunchKernelGGL((gh::attn_mfma_balanced_kernel<false, false, 2>), grid, block, lds, s, a);
-    } else if (a.tokens > 1) {
-      if (bf16)
-        hipLaunchKernelGGL((gh::attn_mfma_balanced_kernel<true, true, 1>), grid, block, lds, s, a);
-      else
-        hipLaunchKernelGGL((gh::attn_mfma_balanced_kernel<false, true, 1>), grid, block, lds, s, a);
-    } else {
-      if (bf16)
-        hipLaunchKernelGGL((gh::attn_mfma_balanced_kernel<true, false, 1>), grid, block, lds, s, a);
-      else
-        hipLaunchKernelGGL((gh::attn_mfma_balanced_kernel<false, false, 1>), grid, block, lds, s, a);
-    }
+    launch_balanced(a, bf16, a.tokens > 1, pl.passes_per_strip, pl.share > 1, lds, s);
   } else if (pl.kernel == GH_KERNEL_MFMA) {
     const dim3 grid(a.n_items), block(64);
     if (bf16)

@@ -333,7 +333,10 @@ def _grouped_rows(T):
 
 @pytest.mark.parametrize("dtype", ["bf16", "f16"])
 @pytest.mark.parametrize("H,Hkv,T", [(8, 1, 2), (8, 2, 4), (4, 4, 16), (8, 2, 3), (16, 2, 4),
-                                     (6, 2, 5), (2, 2, 40)])
+                                     (6, 2, 5), (2, 2, 40),
+                                     (8, 2, 12),     # 48 columns: two waves on one stream
+                                     (16, 2, 16),    # 128 columns: four waves on one stream
+                                     (8, 1, 64)])    # 512 columns: four such strips
 def test_token_groups_share_the_slot_stream_and_match_the_oracle(H, Hkv, T, dtype):
     """tokens_per_group = T: the T rows of a group are head columns of the same tiles, each masked
     at its own length.  The result must be the per-row oracle's (causal inside a chunk, zero for
@@ -374,7 +377,7 @@ def test_seeded_sweep_of_token_groups():
     padding rows anywhere around it."""
     rng = np.random.default_rng(20250118)
     for case in range(30):
-        T = int(rng.choice([2, 3, 4, 8, 16, 33]))
+        T = int(rng.choice([2, 3, 4, 8, 16, 33, 64]))
         Hkv = int(rng.choice([1, 2, 4]))
         group = int(rng.choice([1, 2, 3, 4, 8, 16]))
         n_groups = int(rng.choice([1, 2, 5, 20]))
