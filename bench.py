@@ -239,6 +239,9 @@ def main():
     ap.add_argument("--early", action="store_true",
                     help="experiment: gh_decode_attention_out (the attention kernel stores the heads "
                          "one wave covers alone; the merge completes the rest)")
+    ap.add_argument("--one-launch", action="store_true",
+                    help="time the step as one gh_decode_step launch (append + attention + merge "
+                         "fused) instead of gh_kv_append + gh_decode_attention + gh_decode_reduce")
     ap.add_argument("--paged", action="store_true",
                     help="keep the caches in a gh_slot_pool (virtual slots, pages mapped on demand)")
     ap.add_argument("--page-rows", type=int, default=1024)
@@ -350,7 +353,23 @@ def main():
         f"attn_bytes={attn_bytes / 1e9:.3f} GB chunk_rows={chunk_rows} n_chunks={n_chunks} "
         f"workspace={ws.numel() * 4 / 1e6:.1f} MB setup={time.perf_counter() - t0:.1f} s")
 
+    # gh_decode_step does not take batches whose entries share a slot (prefill chunks).
+    one_launch = args.one_launch
+    assert not (one_launch and (args.mixed or args.prefill or args.group or args.early))
+    if one_launch:
+        G.check(G.gh_decode_step_init(p, ws))
+
     def step(events=None):
+        if one_launch:
+            if events is not None:
+                events[0].record()
+            G.check(G.gh_decode_step(p, inp["q"], inp["k_new"], inp["v_new"], inp["k_cache"],
+                                     inp["v_cache"], inp["slot_id"], inp["pos"], ws, out,
+                                     G.GH_OUT_NATIVE if args.out16 else G.GH_OUT_F32))
+            if events is not None:
+                events[1].record()
+                events[2].record()
+            return
         G.check(G.gh_kv_append(p, inp["k_cache"], inp["v_cache"], inp["k_new"], inp["v_new"],
                                inp["slot_id"], inp["pos"], None))
         if events is not None:
@@ -389,8 +408,11 @@ def main():
     red_ms = np.array([e[1].elapsed_time(e[2]) for e in evs])
     ms_per_step = elapsed / args.steps * 1e3
     attn_avg_s = float(attn_ms.mean()) * 1e-3
-    achieved = attn_bytes / attn_avg_s / 1e9
-    log(f"step {ms_per_step:.4f} ms | attention mean {attn_ms.mean():.4f} ms median "
+    # the one-launch kernel does the whole sequence-step: its algorithmic bytes are the step's
+    # (K/V rows, q, the result, the appended rows in and out), not the attention's alone
+    kernel_bytes = step_bytes if one_launch else attn_bytes
+    achieved = kernel_bytes / attn_avg_s / 1e9
+    log(f"step {ms_per_step:.4f} ms | {'step kernel' if one_launch else 'attention'} mean {attn_ms.mean():.4f} ms median "
         f"{np.median(attn_ms):.4f} min {attn_ms.min():.4f} | reduce mean {red_ms.mean():.4f} ms | "
         f"attention {achieved:.0f} GB/s = {achieved / HBM_PEAK_GBS * 100:.1f}% of {HBM_PEAK_GBS:.0f} | "
         f"whole step {step_bytes / (elapsed / args.steps) / 1e9:.0f} GB/s | "
@@ -414,7 +436,7 @@ def main():
         log(f"HIP graph replay: {graph_ms:.4f} ms per step (eager {ms_per_step:.4f})")
 
     plain = args.kernel == "auto" and not (
-        args.chunk_rows or args.batch or args.const_len or args.capacity or args.paged or args.mixed
+        args.one_launch or args.chunk_rows or args.batch or args.const_len or args.capacity or args.paged or args.mixed
         or args.prefill or args.group or args.out16 or args.early)
     traffic, traffic_source = (args.traffic_bytes, "command line") if args.traffic_bytes is not None \
         else measured_traffic(w.name) if plain else (None, None)
@@ -430,8 +452,9 @@ def main():
                                f"H_kv={w.n_kv_heads}, d={w.head_dim}, lengths={list(w.lengths)}, "
                                f"seed={w.seed}",
                    "kernel": args.kernel, "chunk_rows": chunk_rows, "n_chunks": n_chunks,
-                   "step": "gh_kv_append + gh_decode_attention" + ("_out" if args.early else "") + " + "
-                           + ("gh_decode_reduce_native" if args.out16 else "gh_decode_reduce"),
+                   "step": ("gh_decode_step (append + attention + merge in one launch)" if one_launch
+                            else "gh_kv_append + gh_decode_attention" + ("_out" if args.early else "")
+                            + " + " + ("gh_decode_reduce_native" if args.out16 else "gh_decode_reduce")),
                    "paged_slots": paged_info, "hip_graph_ms_per_step": graph_ms,
                    "step_algorithmic_bytes": step_bytes,
                    "step_GBps": step_bytes / (elapsed / args.steps) / 1e9,
@@ -439,11 +462,11 @@ def main():
                    "attention_ms_median": float(np.median(attn_ms)),
                    "attention_ms_min": float(attn_ms.min()),
                    "reduce_ms": float(red_ms.mean())},
-        "roofline": {"bound": "hbm", "kernel": "gh_decode_attention",
+        "roofline": {"bound": "hbm", "kernel": "gh_decode_step" if one_launch else "gh_decode_attention",
                      "achieved": achieved, "peak": HBM_PEAK_GBS, "unit": "GB/s",
                      "frac": achieved / HBM_PEAK_GBS,
                      "traffic": traffic, "traffic_source": traffic_source,
-                     "algorithmic_bytes_per_launch": attn_bytes,
+                     "algorithmic_bytes_per_launch": kernel_bytes,
                      "avg_launch_ms": float(attn_ms.mean())},
     }
     if not args.no_cpu_baseline:

@@ -148,7 +148,8 @@ const char* gh_status_string(int32_t status);
  *                         (0 if the problem is invalid or batch == 0).
  *
  * Workspace layout (base 16-byte aligned), with d = head_dim:
- *   float o[B][H][C][d], float m[B][H][C], float l[B][H][C], int32 n[B][H]
+ *   float o[B][H][C][d], float m[B][H][C], float l[B][H][C], int32 n[B][H],
+ *   int32 arrive[B][H] (gh_decode_step only)
  * n = how many of a head's C records are in use (records at index >= n are
  * unspecified and ignored by the merge); -1 = the head's result is already in
  * the output (gh_decode_attention_out).
@@ -256,6 +257,41 @@ int32_t gh_decode_reduce(const gh_problem* p, const void* workspace,
  */
 int32_t gh_decode_reduce_native(const gh_problem* p, const void* workspace,
                                 const int32_t* ctx_len, void* out16, void* hip_stream);
+
+/*
+ * The whole stage F2(C_k, qkv) -> C_k, x'_k of Section 2.1 in ONE launch, for a
+ * batch of one token per slot (plain decode): append, attention and merge.  It
+ * computes what gh_kv_append + gh_decode_attention(ctx_len = pos + 1) +
+ * gh_decode_reduce / gh_decode_reduce_native compute -- the appended rows bit
+ * for bit, the result up to fp32 rounding order -- without the two extra
+ * launches, which at the batch sizes of a Tier-2 node (tens of prompts,
+ * Section 5.2 / Table 2) cost as much as the attention itself.
+ *   - pos[b]: position of sequence b's new row; rows [0, pos[b]] are attended.
+ *     The wave that reaches the end of a context reads the new row from k_new /
+ *     v_new (never from the cache) and writes it to row pos[b] of the slot.
+ *   - Slot ids must be UNIQUE within the batch (no prefill chunks here: a
+ *     token's row would be appended while another token's wave reads the slot),
+ *     and tokens_per_group must be 0 or 1 (GH_ERR_UNSUPPORTED).
+ *   - A slot id outside [0, n_slots) or a position outside
+ *     [0, min(slot_capacity, max_ctx_len)) skips the sequence: nothing is
+ *     appended, its result is zero, and GH_DEV_BAD_SLOT / GH_DEV_BAD_POS is OR-ed
+ *     into *dev_status when that is non-null (the caller clears it).
+ *   - workspace: gh_decode_workspace_bytes(p) bytes.  Its arrival counters (one
+ *     word per context strip; the wave that delivers the last partial record of
+ *     a context merges them) must be zero when a launch begins: call
+ *     gh_decode_step_init once on a fresh workspace; every gh_decode_step leaves
+ *     them zero again.  Two steps that overlap in time need two workspaces.
+ *   - out / out_kind as for gh_decode_attention_out; every row of `out` is
+ *     written.  Deterministic for given inputs (fixed summation order).
+ *   - With a fixed split (chunk_rows > 0), GH_KERNEL_VALU or a batch beyond the
+ *     balanced split the call issues the three kernels instead, same result.
+ */
+int32_t gh_decode_step_init(const gh_problem* p, void* workspace, size_t workspace_bytes,
+                            void* hip_stream);
+int32_t gh_decode_step(const gh_problem* p, const void* q, const void* k_new, const void* v_new,
+                       void* k_cache, void* v_cache, const int32_t* slot_id, const int32_t* pos,
+                       void* workspace, size_t workspace_bytes, void* out, int32_t out_kind,
+                       int32_t* dev_status, void* hip_stream);
 
 /*
  * For callers that cannot allocate device memory or hand over a workspace: code

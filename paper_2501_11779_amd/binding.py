@@ -24,7 +24,7 @@ GH_DEV_BAD_SLOT, GH_DEV_BAD_POS = 1, 2
 EXPORTS = ("gh_status_string", "gh_decode_chunk_rows", "gh_decode_num_chunks",
            "gh_decode_workspace_bytes", "gh_kv_append", "gh_decode_attention", "gh_decode_reduce",
            "gh_decode_reduce_native", "gh_decode_split_plan", "gh_decode_attention_out",
-           "gh_decode_attention_static")
+           "gh_decode_attention_static", "gh_decode_step", "gh_decode_step_init")
 GH_OUT_F32, GH_OUT_NATIVE = 0, 1
 GH_PROBE_STORE_PLAIN, GH_PROBE_STORE_NT, GH_PROBE_STORE_WRITE_THROUGH = 0, 1, 2
 POOL_EXPORTS = ("gh_slot_pool_create", "gh_slot_pool_destroy", "gh_slot_pool_k", "gh_slot_pool_v",
@@ -105,6 +105,10 @@ def lib():
         L.gh_decode_attention_out.argtypes = [P, V, V, V, V, V, V, C.c_size_t, V, C.c_int32, V]
         L.gh_decode_attention_static.restype = C.c_int32
         L.gh_decode_attention_static.argtypes = [P, V, V, V, V, V, V, C.c_int32, V]
+        L.gh_decode_step_init.restype = C.c_int32
+        L.gh_decode_step_init.argtypes = [P, V, C.c_size_t, V]
+        L.gh_decode_step.restype = C.c_int32
+        L.gh_decode_step.argtypes = [P, V, V, V, V, V, V, V, V, C.c_size_t, V, C.c_int32, V, V]
         L.gh_decode_reduce.restype = C.c_int32
         L.gh_decode_reduce.argtypes = [P, V, V, V, V]
         L.gh_decode_reduce_native.restype = C.c_int32
@@ -207,6 +211,22 @@ def gh_decode_attention_static(p, q, k_cache, v_cache, slot_id, ctx_len, out, ou
                                             _stream(stream))
 
 
+def gh_decode_step_init(p, workspace, workspace_bytes=None, stream=None):
+    if workspace_bytes is None:
+        workspace_bytes = workspace.numel() * workspace.element_size()
+    return lib().gh_decode_step_init(C.byref(p), _ptr(workspace), workspace_bytes, _stream(stream))
+
+
+def gh_decode_step(p, q, k_new, v_new, k_cache, v_cache, slot_id, pos, workspace, out, out_kind,
+                   dev_status=None, workspace_bytes=None, stream=None):
+    if workspace_bytes is None:
+        workspace_bytes = workspace.numel() * workspace.element_size()
+    return lib().gh_decode_step(C.byref(p), _ptr(q), _ptr(k_new), _ptr(v_new), _ptr(k_cache),
+                                _ptr(v_cache), _ptr(slot_id), _ptr(pos), _ptr(workspace),
+                                workspace_bytes, _ptr(out), int(out_kind), _ptr(dev_status),
+                                _stream(stream))
+
+
 def gh_decode_reduce(p, workspace, ctx_len, out, stream=None):
     return lib().gh_decode_reduce(C.byref(p), _ptr(workspace), _ptr(ctx_len), _ptr(out),
                                   _stream(stream))
@@ -270,6 +290,22 @@ def decode_step(p, inp, workspace, out, dev_status=None, stream=None, append=Tru
                                   inp["ctx_len"], workspace, None, stream))
     check((gh_decode_reduce_native if native else gh_decode_reduce)(p, workspace, inp["ctx_len"],
                                                                     out, stream))
+    return out
+
+
+def alloc_step_workspace(p, device="cuda", stream=None):
+    """A workspace for gh_decode_step: allocated and its arrival counters cleared."""
+    ws = alloc_workspace(p, device)
+    check(gh_decode_step_init(p, ws, None, stream))
+    return ws
+
+
+def decode_step_one_launch(p, inp, workspace, out, dev_status=None, stream=None):
+    """gh_decode_step on a make_inputs() dict; `workspace` from alloc_step_workspace()."""
+    check(gh_decode_step(p, inp["q"], inp["k_new"], inp["v_new"], inp["k_cache"], inp["v_cache"],
+                         inp["slot_id"], inp["pos"], workspace, out,
+                         GH_OUT_F32 if out.dtype == torch.float32 else GH_OUT_NATIVE, dev_status,
+                         None, stream))
     return out
 
 

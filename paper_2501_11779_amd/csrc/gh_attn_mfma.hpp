@@ -356,8 +356,15 @@ __device__ __forceinline__ void store_record(const AttnArgs& a, int b, int g, in
   }
   if (hn < nh && c == 0) {
     const int64_t pi = column_index(a, b, g, pass, hn) * a.n_chunks + slot;
-    a.ws_m[pi] = m;
-    a.ws_l[pi] = l;
+    if (a.ctx_bias) {
+      // one-launch step: another wave of this launch reads the record, possibly through another
+      // L2; device-scope stores go through to memory like the rows above
+      __hip_atomic_store(a.ws_m + pi, m, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+      __hip_atomic_store(a.ws_l + pi, l, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+    } else {
+      a.ws_m[pi] = m;
+      a.ws_l[pi] = l;
+    }
   }
 }
 
@@ -406,6 +413,135 @@ __device__ __forceinline__ void store_final(const AttnArgs& a, int b, int g, int
         const u32x2 hi = {pack2<BF16>(x[k + 4][0], x[k + 4][1]), pack2<BF16>(x[k + 4][2], x[k + 4][3])};
         __builtin_amdgcn_raw_buffer_store_b64(lo, dst, at * 2, 0, kWriteThrough);
         __builtin_amdgcn_raw_buffer_store_b64(hi, dst, (at + 32) * 2, 0, kWriteThrough);
+      }
+    }
+  }
+}
+
+// The append of the one-launch step.  There the row a step appends is a tile of its own at the end
+// of the strip, loaded from k_new / v_new like any tile with a single row (every lane's row clamps
+// to it).  The lanes whose registers stand for in-tile row `top` (0 for that tile; not one of the
+// clamped copies) write the row to its place in the caches.  krow / vrow: address of that row in
+// the K and the V strip.  A bit copy of what was loaded.
+__device__ __forceinline__ void store_new_row(const TileRegs& t, char* krow, char* vrow, int top,
+                                              const LaneGeom& lg) {
+#pragma unroll
+  for (int T = 0; T < 2; ++T) {
+#pragma unroll
+    for (int ab = 0; ab < 2; ++ab) {
+      if (lg.krow + 16 * T + 2 * ab == top) {
+#pragma unroll
+        for (int half = 0; half < 2; ++half)
+          *reinterpret_cast<u32x4*>(krow + lg.kcol + 128 * half) = t.k[T][half][ab];
+      }
+    }
+  }
+#pragma unroll
+  for (int e = 0; e < 8; ++e) {
+    if (lg.vrow + 16 * (e >> 2) + 4 * (e & 3) == top)
+      *reinterpret_cast<u32x4*>(vrow + lg.vcol) = t.v[e];
+  }
+}
+
+// Merge of the first n_rec partial records of the nh head columns of one pass (the rule of
+// decode_reduce_kernel), by one wave, for all columns at once: lanes 0-31 take the even columns,
+// lanes 32-63 the odd ones, four output columns each.  NJ = column pairs (4 for up to 8 columns, 8
+// for up to 16), R = records per batch: the records are read R at a time -- all loads of a batch in
+// flight together, one memory round trip -- and folded into running (exponent, sum, row) triples.
+// The order of the arithmetic is fixed by the record index alone.
+// An address that is the same in every lane, moved to scalar registers.
+__device__ __forceinline__ float* uniform_address(float* p) {
+  const uint64_t v = reinterpret_cast<uint64_t>(p);
+  const uint32_t lo = (uint32_t)__builtin_amdgcn_readfirstlane((int)(uint32_t)v);
+  const uint32_t hi = (uint32_t)__builtin_amdgcn_readfirstlane((int)(uint32_t)(v >> 32));
+  return reinterpret_cast<float*>(((uint64_t)hi << 32) | lo);
+}
+
+template <bool BF16, int NJ, int R>
+__device__ __forceinline__ void merge_columns(const AttnArgs& a, int b, int g, int pass, int nh,
+                                              int n_rec, int lane) {
+  typedef uint32_t u32x2 __attribute__((ext_vector_type(2)));
+  const int half = lane >> 5, cg = lane & 31;
+  // The records were written by other waves of this launch, with write-through stores: they are
+  // loaded at device scope, past the caches that are not kept coherent between the chip's L2
+  // slices.  (Buffer loads carry that policy; the records of the pass's columns lie at increasing
+  // addresses from the first column's, within 2 GiB -- the launch checks that.)
+  // (b, g and pass are the same in every lane; say so, or each load becomes a loop over lanes)
+  const int64_t first = column_index(a, __builtin_amdgcn_readfirstlane(b), __builtin_amdgcn_readfirstlane(g),
+                                     __builtin_amdgcn_readfirstlane(pass), 0);
+  const __amdgpu_buffer_rsrc_t rec = __builtin_amdgcn_make_buffer_rsrc(
+      uniform_address(a.ws_o + first * a.n_chunks * kHeadDim), 0, 0x7fffffff, kRawBufferFlags);
+  const __amdgpu_buffer_rsrc_t rec_m = __builtin_amdgcn_make_buffer_rsrc(
+      uniform_address(a.ws_m + first * a.n_chunks), 0, 0x7fffffff, kRawBufferFlags);
+  const __amdgpu_buffer_rsrc_t rec_l = __builtin_amdgcn_make_buffer_rsrc(
+      uniform_address(a.ws_l + first * a.n_chunks), 0, 0x7fffffff, kRawBufferFlags);
+  float M[NJ], L[NJ];
+  f32x4 acc[NJ];
+  int rel[NJ];                                                   // first record of the column, from `first`
+#pragma unroll
+  for (int j = 0; j < NJ; ++j) {
+    const int hc = 2 * j + half;
+    // padding lanes shadow column 0
+    rel[j] = (int)((column_index(a, b, g, pass, hc < nh ? hc : 0) - first) * a.n_chunks);
+    M[j] = kNegInf;
+    L[j] = 0.f;
+    acc[j] = f32x4{0.f, 0.f, 0.f, 0.f};
+  }
+  for (int r0 = 0; r0 < n_rec; r0 += R) {
+    float mm[NJ][R], ll[NJ][R];
+    f32x4 oo[NJ][R];
+#pragma unroll
+    for (int j = 0; j < NJ; ++j) {
+#pragma unroll
+      for (int u = 0; u < R; ++u) {
+        const int r = r0 + u < n_rec ? r0 + u : n_rec - 1;       // past the end: the last one again, weight 0
+        const int at = rel[j] + r;
+        mm[j][u] = __builtin_bit_cast(float, __builtin_amdgcn_raw_buffer_load_b32(rec_m, at * 4, 0, kWriteThrough));
+        const float lr = __builtin_bit_cast(float, __builtin_amdgcn_raw_buffer_load_b32(rec_l, at * 4, 0, kWriteThrough));
+        ll[j][u] = r0 + u < n_rec ? lr : 0.f;
+        oo[j][u] = __builtin_bit_cast(f32x4, __builtin_amdgcn_raw_buffer_load_b128(
+            rec, (at * kHeadDim + 4 * cg) * 4, 0, kWriteThrough));
+      }
+    }
+#pragma unroll
+    for (int j = 0; j < NJ; ++j) {
+      float mx = M[j];
+#pragma unroll
+      for (int u = 0; u < R; ++u) {
+        mm[j][u] = ll[j][u] > 0.f ? mm[j][u] : kNegInf;          // a record without rows carries no exponent
+        mx = fmaxf(mx, mm[j][u]);
+      }
+      if (mx != kNegInf) {
+        const float keep = fast_exp2(M[j] - mx);                 // 0 while nothing has been folded in
+        f32x4 x = acc[j] * keep;
+        float sum = L[j] * keep;
+#pragma unroll
+        for (int u = 0; u < R; ++u) {
+          const float w = fast_exp2(mm[j][u] - mx);
+          if (w > 0.f) {                                         // an empty record's row is unspecified
+#pragma unroll
+            for (int e = 0; e < 4; ++e) x[e] = fmaf(w, oo[j][u][e], x[e]);
+          }
+          sum = fmaf(w, ll[j][u], sum);
+        }
+        acc[j] = x;
+        L[j] = sum;
+        M[j] = mx;
+      }
+    }
+  }
+#pragma unroll
+  for (int j = 0; j < NJ; ++j) {
+    if (2 * j + half < nh) {
+      const int64_t row = first + rel[j] / a.n_chunks;
+      f32x4 x;
+#pragma unroll
+      for (int e = 0; e < 4; ++e) x[e] = L[j] > 0.f ? acc[j][e] / L[j] : 0.f;
+      if (a.out_kind == 1) {
+        *reinterpret_cast<f32x4*>(static_cast<float*>(a.out) + row * kHeadDim + 4 * cg) = x;
+      } else {
+        const u32x2 w = {pack2<BF16>(x[0], x[1]), pack2<BF16>(x[2], x[3])};
+        *reinterpret_cast<u32x2*>(static_cast<uint16_t*>(a.out) + row * kHeadDim + 4 * cg) = w;
       }
     }
   }
@@ -516,8 +652,10 @@ struct TileCursor {
 // state and accumulators per pass, one stream of tiles for all): 1 for decode, 2 for token groups
 // with more than 16 head columns, at one wave per SIMD instead of two.
 // SHARED: the waves of a workgroup walk the same tiles in sets of a.share (> 1), see below.
-template <bool BF16, bool GROUPED, int P, bool SHARED>
+// FUSED: the whole step in one launch (see AttnArgs): append, attention and merge.
+template <bool BF16, bool GROUPED, int P, bool SHARED, bool FUSED>
 __global__ __launch_bounds__(256, P == 1 ? 2 : 1) void attn_mfma_balanced_kernel(const AttnArgs a) {
+  static_assert(!(FUSED && GROUPED), "the one-launch step is for batches of one token per slot");
   constexpr int kThreads = 256;
   extern __shared__ uint32_t lds[];
   __shared__ uint32_t part[kThreads];
@@ -533,6 +671,14 @@ __global__ __launch_bounds__(256, P == 1 ? 2 : 1) void attn_mfma_balanced_kernel
     for (int t = 0; t < a.tokens; ++t) {
       const int st = a.slot_id[(int64_t)b * a.tokens + t];
       int nt = a.ctx_len[(int64_t)b * a.tokens + t];
+      if constexpr (FUSED) {
+        // ctx_len[] holds the position of the new row: it must lie inside the slot and inside the
+        // declared bound, else the sequence is skipped (no append, result zero) and flagged
+        const bool bad_slot = st < 0 || st >= a.n_slots, bad_pos = nt < 0 || nt >= a.row_limit;
+        if ((bad_slot || bad_pos) && a.dev_status && blockIdx.x == 0)
+          atomicOr(a.dev_status, (bad_slot ? 1 : 0) | (bad_pos ? 2 : 0));
+        nt = bad_pos ? 0 : nt + 1;
+      }
       nt = nt < a.row_limit ? nt : a.row_limit;
       if (st < 0 || st >= a.n_slots || nt <= 0) continue;
       if (n == 0) slot = st;                     // the first live token row names the group's slot
@@ -540,7 +686,8 @@ __global__ __launch_bounds__(256, P == 1 ? 2 : 1) void attn_mfma_balanced_kernel
     }
     rows[b] = n;
     slots[b] = slot;
-    cum[b + 1] = (n > 0 ? (uint32_t)(n + 31) >> 5 : 1u) * spb;
+    // (one-launch step: the cached rows 0 .. n-2 in tiles, then the new row as a tile of its own)
+    cum[b + 1] = (n > 0 ? ((uint32_t)(n - (FUSED ? 1 : 0) + 31) >> 5) + (FUSED ? 1u : 0u) : 1u) * spb;
   }
   if (tid == 0) cum[0] = 0;
   __syncthreads();
@@ -647,6 +794,15 @@ __global__ __launch_bounds__(256, P == 1 ? 2 : 1) void attn_mfma_balanced_kernel
       kt = reinterpret_cast<const char*>(a.k_cache + at);
       vt = reinterpret_cast<const char*>(a.v_cache + at);
       rows = cu.n - row0;
+      if constexpr (FUSED) {
+        rows = cu.n - 1 - row0;                                // the cache holds rows 0 .. n-2
+        if (cu.lt + 1 == cu.tiles) {                           // the last tile is the new row alone
+          const int64_t from = (int64_t)cu.b * a.new_batch_stride + (int64_t)g * kHeadDim;
+          kt = reinterpret_cast<const char*>(a.k_new + from);
+          vt = reinterpret_cast<const char*>(a.v_new + from);
+          rows = 1;
+        }
+      }
     }
     // (a wave of its own reads every row once: keep the stream out of the caches' way; when several
     // waves ask for the same rows, let the cache keep them)
@@ -736,17 +892,45 @@ __global__ __launch_bounds__(256, P == 1 ? 2 : 1) void attn_mfma_balanced_kernel
     l[i] = 0.f;
   }
 
+  // One-launch step: the strips this wave wrote a record for (at most the one its share begins in
+  // and the one it ends in), to be counted as arrived once the wave has nothing in flight.
+  uint32_t part_strip[2] = {0u, 0u};                           // b * spb + sib
+  int part_b[2] = {0, 0}, part_records[2] = {0, 0};
+  int n_part = 0;
+
   // One tile of arithmetic; closes the record when the tile ends this wave's piece of the strip.
   auto compute = [&](const TileRegs& regs) {
     // (a pass without columns runs on a zero operand; its results are never stored)
-    if (cp.n > 0)
-      process_tile<BF16, P>(regs, qop, acc, m, l, a.scale_log2e, (int)cp.lt * 32, lim, c);
     const bool strip_end = cp.lt + 1 == cp.tiles;
+    if (cp.n > 0) {
+      // (one-launch step: the strip's last tile is the new row, whose row number is n - 1)
+      if constexpr (FUSED) {
+        // the cached rows end at n - 2 (what a cache tile holds beyond is a clamped copy); the
+        // strip's last tile is the new row alone, row number n - 1
+        int upto[P];
+#pragma unroll
+        for (int i = 0; i < P; ++i) upto[i] = strip_end ? lim[i] : lim[i] - 1;
+        process_tile<BF16, P>(regs, qop, acc, m, l, a.scale_log2e,
+                              strip_end ? cp.n - 1 : (int)cp.lt * 32, upto, c);
+      } else {
+        process_tile<BF16, P>(regs, qop, acc, m, l, a.scale_log2e, (int)cp.lt * 32, lim, c);
+      }
+    }
+    if constexpr (FUSED) {
+      // the append: the new row sits in this tile's registers (written by the first pass set only)
+      if (strip_end && cp.n > 0 && cp.sib % (uint32_t)a.n_pass == 0 && wsub == 0) {
+        const int64_t at = (int64_t)cp.slot * a.slot_stride + (int64_t)g * a.head_stride +
+                           row_offset(cp.n - 1, a.row_stride, a.block_stride, a.block_shift, a.block_mask);
+        store_new_row(regs, reinterpret_cast<char*>(const_cast<uint16_t*>(a.k_cache) + at),
+                      reinterpret_cast<char*>(const_cast<uint16_t*>(a.v_cache) + at), 0, lg);
+      }
+    }
     if (strip_end || cp.t + 1 == t_end) {
       const uint32_t strip_t0 = cp.t - cp.lt;                  // global index of the strip's tile 0
       int rec = (int)(gw - strip_t0 / share);
-      if (cp.n > 0) {
+      if (cp.n > 0 || FUSED) {
         // the strip began inside this wave's share and ends here: nothing to merge
+        // (one-launch step: a strip without rows is whole too, and its result is zero)
         const bool whole = a.out_kind != 0 && strip_end && strip_t0 >= t0;
 #pragma unroll
         for (int i = 0; i < P; ++i) {
@@ -756,9 +940,24 @@ __global__ __launch_bounds__(256, P == 1 ? 2 : 1) void attn_mfma_balanced_kernel
           else
             store_record(a, cp.b, g, pass0 + i, nh[i], rec, acc[i], m[i], l[i], hn, c);
         }
+        if (FUSED && !whole) {
+          // (slot 1 when slot 0 is taken: registers, not an indexed array)
+          const uint32_t id = (uint32_t)cp.b * spb + cp.sib;
+          const int records = (int)((strip_t0 + cp.tiles - 1) / share - strip_t0 / share) + 1;
+          if (n_part == 0) {
+            part_strip[0] = id;
+            part_b[0] = cp.b;
+            part_records[0] = records;
+          } else {
+            part_strip[1] = id;
+            part_b[1] = cp.b;
+            part_records[1] = records;
+          }
+          ++n_part;
+        }
         rec = whole ? -1 : rec + 1;
       }
-      if (strip_end && c == 0) {                               // records in use for these heads
+      if (!FUSED && strip_end && c == 0) {                     // records in use for these heads
 #pragma unroll
         for (int i = 0; i < P; ++i)
           if (hn < nh[i]) a.ws_n[column_index(a, cp.b, g, pass0 + i, hn)] = rec;
@@ -824,6 +1023,43 @@ __global__ __launch_bounds__(256, P == 1 ? 2 : 1) void attn_mfma_balanced_kernel
     compute(tb);
     if (cp.t + 1 >= t_end) break;
     advance(cp);
+  }
+
+  if constexpr (FUSED) {
+    // The merge, in the same launch: a strip that several waves covered is finished by the wave
+    // whose record arrives last.  The wave has no tile in flight any more, so waiting for its own
+    // stores costs nothing here; its records are in memory before the arrival is counted, the
+    // counter says how many records were there before, and the wave that finds all the others
+    // there merges (reading them at device scope).
+    // Nobody waits for anybody.  The last arrival also clears the counter for the next launch.
+    if (n_part > 0) {
+      // (records are written through to memory, so "visible" only means "the stores have
+      // completed": a workgroup-scope release waits for them without flushing the L2)
+      __builtin_amdgcn_fence(__ATOMIC_RELEASE, "workgroup");
+#pragma unroll
+      for (int k = 0; k < 2; ++k) {
+        if (k < n_part) {
+          int before = 0;
+          // (waves that share a strip's rows carry different passes: a counter each)
+          if (lane == 0) before = atomicAdd(a.arrive + part_strip[k] * n_share + wave % n_share, 1);
+          before = __builtin_amdgcn_readfirstlane(before);
+          if (before + 1 == part_records[k]) {
+            if (lane == 0)
+              __hip_atomic_store(a.arrive + part_strip[k] * n_share + wave % n_share, 0,
+                                 __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+            __builtin_amdgcn_fence(__ATOMIC_ACQUIRE, "workgroup");
+            int mg, mpass0, mnh[P];
+            pass_of(part_strip[k] % spb, mg, mpass0, mnh);
+#pragma unroll
+            for (int i = 0; i < P; ++i)
+              if (mnh[i] > 8)
+                merge_columns<BF16, 8, 3>(a, part_b[k], mg, mpass0 + i, mnh[i], part_records[k], lane);
+              else if (mnh[i] > 0)
+                merge_columns<BF16, 4, 6>(a, part_b[k], mg, mpass0 + i, mnh[i], part_records[k], lane);
+          }
+        }
+      }
+    }
   }
 }
 

@@ -37,7 +37,23 @@ struct AttnArgs {
   float scale_log2e;                              // scale * log2(e)
   void* out;                                      // final results of heads one wave covers alone
   int32_t out_kind;                               // 0 none, 1 fp32, 2 binary16, 3 bfloat16
+  // The whole step in one launch (gh_decode_step): ctx_len[] then holds the positions of the new
+  // rows (rows attended = position + 1, ctx_bias = 1), the new rows are taken from k_new / v_new
+  // and written into the caches by the wave that reaches them, and the wave that delivers the
+  // last record of a strip merges the strip's records (arrival counters, zero between launches).
+  int32_t ctx_bias;                               // 0, or 1 when ctx_len[] holds positions
+  const uint16_t* k_new;                          // [B, H_kv, 128]
+  const uint16_t* v_new;
+  int64_t new_batch_stride;                       // elements between sequences in k_new / v_new
+  int32_t* arrive;                                // [B * H_kv * n_pass]
+  int32_t* dev_status;                            // nullable
 };
+
+// Clears n 32-bit words (a kernel, not a memset: it can be captured into a graph).
+__global__ __launch_bounds__(256) void zero_words_kernel(int32_t* p, int64_t n) {
+  const int64_t i = (int64_t)blockIdx.x * 256 + threadIdx.x;
+  if (i < n) p[i] = 0;
+}
 
 // Offset of row r inside a (slot, head) strip.  Blocked layouts place block r >> shift at that
 // multiple of block_stride and the rows of a block row_stride apart; a plain layout is the case
@@ -90,7 +106,8 @@ __device__ __forceinline__ Item decode_item(const AttnArgs& a, int item) {
   const int left = a.group - it.pass * a.heads_per_pass;
   it.nh = left < a.heads_per_pass ? left : a.heads_per_pass;
   const int slot = a.slot_id[it.b];
-  int n = a.ctx_len[it.b];
+  int n = a.ctx_len[it.b] + a.ctx_bias;
+  if (a.ctx_bias && (n <= 0 || n > a.row_limit)) n = 0;   // a position out of range: skipped
   n = n < a.row_limit ? n : a.row_limit;
   if (slot < 0 || slot >= a.n_slots) n = 0;
   it.r0 = it.chunk * a.chunk_rows;

@@ -151,7 +151,8 @@ Plan make_plan(const gh_problem* p) {
   const int share = sets >= 3 ? 4 : sets;
   const int n_strip = (sets + share - 1) / share;
   const int64_t strips = (int64_t)(groups > 0 ? groups : 1) * p->n_kv_heads * n_strip;
-  const int64_t max_tiles = p->max_ctx_len > 0 ? (p->max_ctx_len + 31) / 32 : 1;
+  // (+ 1: the one-launch step walks the appended row as a tile of its own behind the cached rows)
+  const int64_t max_tiles = (p->max_ctx_len > 0 ? (p->max_ctx_len + 31) / 32 : 1) + 1;
   if (pl.kernel == GH_KERNEL_MFMA && p->chunk_rows == 0 && groups <= kBalancedMaxBatch &&
       strips * max_tiles < 0x7fffffff) {
     // Records per head: enough for the longest strip when strips are up to four times the
@@ -175,28 +176,34 @@ Plan make_plan(const gh_problem* p) {
   return pl;
 }
 
+// o, m, l of every record, the record counts, and the arrival counters of the one-launch step
+// (one per strip; there are never more strips than heads)
 size_t workspace_floats(const gh_problem* p, const Plan& pl) {
-  return (size_t)p->batch * p->n_q_heads * ((size_t)pl.n_chunks * (gh::kHeadDim + 2) + 1);
+  return (size_t)p->batch * p->n_q_heads * ((size_t)pl.n_chunks * (gh::kHeadDim + 2) + 2);
 }
 
 // Instantiations of the balanced kernel: dtype x (token groups) x (one pass per wave | two passes,
 // alone or with the workgroup's waves sharing a stream).
-template <bool BF16, bool GROUPED>
+template <bool BF16, bool GROUPED, bool FUSED>
 void launch_balanced_as(const gh::AttnArgs& a, int passes, bool shared, size_t lds, hipStream_t s) {
   const dim3 grid(a.n_workers * a.share / 4), block(256);
   if (passes == 1)
-    hipLaunchKernelGGL((gh::attn_mfma_balanced_kernel<BF16, GROUPED, 1, false>), grid, block, lds, s, a);
+    hipLaunchKernelGGL((gh::attn_mfma_balanced_kernel<BF16, GROUPED, 1, false, FUSED>), grid, block, lds, s, a);
   else if (!shared)
-    hipLaunchKernelGGL((gh::attn_mfma_balanced_kernel<BF16, GROUPED, 2, false>), grid, block, lds, s, a);
+    hipLaunchKernelGGL((gh::attn_mfma_balanced_kernel<BF16, GROUPED, 2, false, FUSED>), grid, block, lds, s, a);
   else
-    hipLaunchKernelGGL((gh::attn_mfma_balanced_kernel<BF16, GROUPED, 2, true>), grid, block, lds, s, a);
+    hipLaunchKernelGGL((gh::attn_mfma_balanced_kernel<BF16, GROUPED, 2, true, FUSED>), grid, block, lds, s, a);
 }
-void launch_balanced(const gh::AttnArgs& a, bool bf16, bool grouped, int passes, bool shared,
-                     size_t lds, hipStream_t s) {
-  if (bf16 && grouped) launch_balanced_as<true, true>(a, passes, shared, lds, s);
-  else if (bf16) launch_balanced_as<true, false>(a, passes, shared, lds, s);
-  else if (grouped) launch_balanced_as<false, true>(a, passes, shared, lds, s);
-  else launch_balanced_as<false, false>(a, passes, shared, lds, s);
+// fused: the one-launch step (never with token groups)
+void launch_balanced(const gh::AttnArgs& a, bool bf16, bool grouped, bool fused, int passes,
+                     bool shared, size_t lds, hipStream_t s) {
+  if (fused) {
+    if (bf16) launch_balanced_as<true, false, true>(a, passes, shared, lds, s);
+    else launch_balanced_as<false, false, true>(a, passes, shared, lds, s);
+  } else if (bf16 && grouped) launch_balanced_as<true, true, false>(a, passes, shared, lds, s);
+  else if (bf16) launch_balanced_as<true, false, false>(a, passes, shared, lds, s);
+  else if (grouped) launch_balanced_as<false, true, false>(a, passes, shared, lds, s);
+  else launch_balanced_as<false, false, false>(a, passes, shared, lds, s);
 }
 
 template <bool BF16>
@@ -300,11 +307,23 @@ int32_t gh_kv_append(const gh_problem* p, void* k_cache, void* v_cache, const vo
 
 namespace {
 
-// out_kind: 0 = no early results, 1 = fp32, 2 = the problem's 16-bit type
+// What the one-launch step adds to an attention launch (null k_new: an ordinary launch).
+struct StepInputs {
+  const void* k_new = nullptr;
+  const void* v_new = nullptr;
+  int32_t* dev_status = nullptr;
+};
+
+// A wave of the one-launch step covers at least this many tiles when the batch is small: fewer,
+// longer pieces per strip keep the merge at its end short (it reads every piece's record).
+constexpr int kStepMinShare = 8;
+
+// out_kind: 0 = no early results, 1 = fp32, 2 = the problem's 16-bit type.  With `step` the array
+// ctx_len holds the positions of the new rows.
 int32_t launch_attention(const gh_problem* p, const void* q, const void* k_cache,
                          const void* v_cache, const int32_t* slot_id, const int32_t* ctx_len,
                          void* workspace, size_t workspace_bytes, void* out, int out_kind,
-                         void* hip_stream) {
+                         void* hip_stream, const StepInputs& step = StepInputs()) {
   const int32_t st = check_problem(p);
   if (st != GH_OK) return st;
   if (p->batch == 0) return GH_OK;
@@ -331,6 +350,13 @@ int32_t launch_attention(const gh_problem* p, const void* q, const void* k_cache
   a.ws_m = a.ws_o + nrec * gh::kHeadDim;
   a.ws_l = a.ws_m + nrec;
   a.ws_n = reinterpret_cast<int32_t*>(a.ws_l + nrec);
+  a.arrive = a.ws_n + (size_t)p->batch * p->n_q_heads;
+  a.ctx_bias = step.k_new ? 1 : 0;
+  a.k_new = static_cast<const uint16_t*>(step.k_new);
+  a.v_new = static_cast<const uint16_t*>(step.v_new);
+  a.new_batch_stride =
+      p->new_batch_stride ? p->new_batch_stride : (int64_t)p->n_kv_heads * p->head_dim;
+  a.dev_status = step.dev_status;
   a.slot_stride = p->slot_stride;
   a.head_stride = p->head_stride;
   a.row_stride = p->row_stride;
@@ -350,7 +376,7 @@ int32_t launch_attention(const gh_problem* p, const void* q, const void* k_cache
   a.n_items = (int32_t)items;
   a.batch = p->batch / a.tokens;                 // groups
   a.n_workers = pl.n_workers;
-  a.min_share = pl.min_share;
+  a.min_share = step.k_new && pl.min_share < kStepMinShare ? kStepMinShare : pl.min_share;
   a.share = pl.share;
   a.scale_log2e = p->scale * 1.44269504088896340736f;
   a.out = out;
@@ -360,7 +386,8 @@ int32_t launch_attention(const gh_problem* p, const void* q, const void* k_cache
   const bool bf16 = p->dtype == GH_BF16;
   if (pl.balanced) {
     const size_t lds = (size_t)(3 * a.batch + 1) * sizeof(uint32_t);
-    launch_balanced(a, bf16, a.tokens > 1, pl.passes_per_strip, pl.share > 1, lds, s);
+    launch_balanced(a, bf16, a.tokens > 1, step.k_new != nullptr, pl.passes_per_strip, pl.share > 1,
+                    lds, s);
   } else if (pl.kernel == GH_KERNEL_MFMA) {
     const dim3 grid(a.n_items), block(64);
     if (bf16)
@@ -473,6 +500,59 @@ int32_t gh_decode_attention_static(const gh_problem* p, const void* q, const voi
                                               out, out_kind, hip_stream);
   if (ast != GH_OK) return ast;
   return launch_reduce(p, ws, out, out_kind == GH_OUT_F32 ? 0 : 1, hip_stream);
+}
+
+int32_t gh_decode_step_init(const gh_problem* p, void* workspace, size_t workspace_bytes,
+                            void* hip_stream) {
+  const int32_t st = check_problem(p);
+  if (st != GH_OK) return st;
+  if (p->batch == 0) return GH_OK;
+  if (!workspace) return GH_ERR_NULL;
+  if (!aligned16(workspace)) return GH_ERR_UNSUPPORTED;
+  const Plan pl = make_plan(p);
+  if (workspace_bytes < workspace_floats(p, pl) * sizeof(float)) return GH_ERR_WORKSPACE;
+  const size_t rows = (size_t)p->batch * p->n_q_heads;
+  int32_t* arrive = static_cast<int32_t*>(workspace) + rows * ((size_t)pl.n_chunks * (gh::kHeadDim + 2) + 1);
+  hipLaunchKernelGGL(gh::zero_words_kernel, dim3((unsigned)((rows + 255) / 256)), dim3(256), 0,
+                     static_cast<hipStream_t>(hip_stream), arrive, (int64_t)rows);
+  return hipGetLastError() == hipSuccess ? GH_OK : GH_ERR_HIP;
+}
+
+int32_t gh_decode_step(const gh_problem* p, const void* q, const void* k_new, const void* v_new,
+                       void* k_cache, void* v_cache, const int32_t* slot_id, const int32_t* pos,
+                       void* workspace, size_t workspace_bytes, void* out, int32_t out_kind,
+                       int32_t* dev_status, void* hip_stream) {
+  if (out_kind != GH_OUT_F32 && out_kind != GH_OUT_NATIVE) return GH_ERR_UNSUPPORTED;
+  const int32_t st = check_problem(p);
+  if (st != GH_OK) return st;
+  if (tokens_per_group(p) > 1) return GH_ERR_UNSUPPORTED;
+  if (p->batch == 0) return GH_OK;
+  if (!q || !k_new || !v_new || !k_cache || !v_cache || !slot_id || !pos || !workspace || !out)
+    return GH_ERR_NULL;
+  if (!aligned16(k_new) || !aligned16(v_new) || !aligned16(out)) return GH_ERR_UNSUPPORTED;
+  if ((int64_t)p->n_q_heads * gh::kHeadDim * 4 > 0x7fffffff) return GH_ERR_UNSUPPORTED;
+  StepInputs step;
+  step.k_new = k_new;
+  step.v_new = v_new;
+  step.dev_status = dev_status;
+  const Plan pl = make_plan(p);
+  if (pl.balanced)
+    return launch_attention(p, q, k_cache, v_cache, slot_id, pos, workspace, workspace_bytes, out,
+                            out_kind == GH_OUT_F32 ? 1 : 2, hip_stream, step);
+  // Fixed split, vector kernel or a batch beyond the balanced split: the same result from the
+  // three kernels, with the same rule for positions out of range.
+  gh_problem bounded = *p;
+  bounded.slot_capacity = p->max_ctx_len < p->slot_capacity ? p->max_ctx_len : p->slot_capacity;
+  const int32_t ast = gh_kv_append(&bounded, k_cache, v_cache, k_new, v_new, slot_id, pos, dev_status,
+                                   hip_stream);
+  if (ast != GH_OK) return ast;
+  StepInputs positions;                 // rows attended = position + 1; the rows are appended already
+  positions.k_new = k_new;
+  positions.v_new = v_new;
+  const int32_t tst = launch_attention(p, q, k_cache, v_cache, slot_id, pos, workspace,
+                                       workspace_bytes, nullptr, 0, hip_stream, positions);
+  if (tst != GH_OK) return tst;
+  return launch_reduce(p, workspace, out, out_kind == GH_OUT_F32 ? 0 : 1, hip_stream);
 }
 
 int32_t gh_decode_reduce(const gh_problem* p, const void* workspace, const int32_t* ctx_len,

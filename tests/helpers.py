@@ -145,3 +145,11 @@ def assert_rounded_within(got_bits, want, dtype, eps, what=""):
     bad = (g < lo) | (g > hi)
     assert not bad.any(), f"{what}: {int(bad.sum())} 16-bit values outside the rounding of want +- {eps}"
     return float((np.asarray(got_bits) == round_f64_to_bits(want, dtype)).mean())
+
+
+def record_counts(ws, batch, n_q_heads):
+    """int32 n[B*H] of a workspace tensor (records in use per head; -1 = finished by the attention
+    kernel): the words before the arrival counters that end the workspace."""
+    import torch
+    rows = batch * n_q_heads
+    return ws.view(torch.int32)[-2 * rows:-rows].cpu().numpy()

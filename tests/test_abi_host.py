@@ -156,7 +156,8 @@ def test_chunk_plan_is_consistent(kernel, B, H, Hkv, maxlen):
     else:
         assert rows == 0                            # balanced split: equal shares per wave
         assert 2 <= n <= 64
-    assert G.gh_decode_workspace_bytes(p) == B * H * (n * (128 + 2) + 1) * 4
+    # o, m, l of every record; the record count and the arrival counter of every head
+    assert G.gh_decode_workspace_bytes(p) == B * H * (n * (128 + 2) + 2) * 4
     # a forced chunk size is taken as given
     p.chunk_rows = 128
     assert G.gh_decode_chunk_rows(p) == 128
@@ -290,6 +291,28 @@ def test_public_headers_are_plain_c(tmp_path):
             res = subprocess.run([cc, *std, "-Wall", "-Wextra", "-Werror", "-fsyntax-only", "-I", inc,
                                   str(src)], capture_output=True, text=True)
             assert res.returncode == 0, f"{h} with {cc}: {res.stderr}"
+
+
+def test_step_call_checks_its_arguments():
+    p = good()
+    a, big = 4096, 1 << 40
+    f = lambda *x: G.lib().gh_decode_step(C.byref(x[0]), *x[1:])
+    args = [p, a, a, a, a, a, a, a, a, big, a, G.GH_OUT_F32, None, None]
+    for missing in (1, 2, 3, 4, 5, 6, 7, 8, 10):
+        bad = list(args)
+        bad[missing] = None
+        assert f(*bad) == G.GH_ERR_NULL, missing
+    bad = list(args); bad[11] = 5
+    assert f(*bad) == G.GH_ERR_UNSUPPORTED
+    bad = list(args); bad[10] = a + 4
+    assert f(*bad) == G.GH_ERR_UNSUPPORTED                        # out not 16-byte aligned
+    bad = list(args); bad[9] = 64
+    assert f(*bad) == G.GH_ERR_WORKSPACE
+    grouped = good(tokens_per_group=2)
+    assert f(grouped, *args[1:]) == G.GH_ERR_UNSUPPORTED
+    assert G.lib().gh_decode_step_init(C.byref(p), None, big, None) == G.GH_ERR_NULL
+    assert G.lib().gh_decode_step_init(C.byref(p), a, 64, None) == G.GH_ERR_WORKSPACE
+    assert G.lib().gh_decode_step_init(C.byref(good(batch=0)), None, 0, None) == G.GH_OK
 
 
 def test_attention_out_checks_its_arguments():

@@ -114,7 +114,7 @@ def test_whole_output_through_the_other_launch_paths(name, variant):
     G.decode_step(p, inp, ws, out, early="early" in variant)
     torch.cuda.synchronize()
     if "early" in variant:
-        n_rec = ws.view(torch.int32)[-w.batch * w.n_q_heads:].cpu().numpy()
+        n_rec = Hh.record_counts(ws, w.batch, w.n_q_heads)
         print(f"{name} {variant}: {(n_rec == -1).mean() * 100:.1f}% of the heads finished by the "
               f"attention kernel", flush=True)
     if not native:
@@ -130,6 +130,35 @@ def test_whole_output_through_the_other_launch_paths(name, variant):
     print(f"{name} {variant}: {same * 100:.3f}% of the 16-bit values identical to the rounded "
           f"oracle", flush=True)
     assert same > 0.995
+
+
+@pytest.mark.parametrize("name", ["c2", "c4", "c5"])
+def test_whole_output_of_the_one_launch_step(name):
+    """gh_decode_step (append + attention + merge in one launch) at full size: the whole output
+    against the oracle, the appended rows in place bit for bit and nothing else in the caches
+    touched (the expectation for the caches is the pre-step copy with the new rows put in by
+    plain indexing; the oracle's own mirror is compared in the three-call test above)."""
+    w = W.WORKLOADS[name]
+    inp = W.make_inputs(w, DEV)
+    want = _want_head_major(name, inp)                      # from the caches before the step
+    k_want, v_want = inp["k_cache"].clone(), inp["v_cache"].clone()
+    slot, pos = inp["slot_id"].long(), inp["pos"].long()
+    k_want[slot, :, pos] = inp["k_new"]
+    v_want[slot, :, pos] = inp["v_new"]
+    p = G.problem_from_inputs(inp)
+    ws = G.alloc_workspace(p, DEV)
+    ws.fill_(float("nan"))
+    G.check(G.gh_decode_step_init(p, ws))
+    out = torch.full((w.batch, w.n_q_heads, w.head_dim), float("nan"), dtype=torch.float32,
+                     device=DEV)
+    G.decode_step_one_launch(p, inp, ws, out)
+    torch.cuda.synchronize()
+    got = out.cpu().numpy().astype(np.float64)
+    _report(name, "one launch", got, want, inp["lengths"])
+    Hh.assert_tight(got, want, f"{name} one launch")
+    assert torch.equal(inp["k_cache"].view(torch.int16), k_want.view(torch.int16))
+    assert torch.equal(inp["v_cache"].view(torch.int16), v_want.view(torch.int16))
+    assert not ws.view(torch.int32)[-w.batch * w.n_q_heads:].any()      # arrival counters at zero
 
 
 @pytest.mark.parametrize("name", ["c4", "c5"])
