@@ -174,7 +174,8 @@ static void scores(const gho_problem* p, const uint16_t* q,
 
 /*
  * Attention by its definition.  q is [B, H, d]; ctx_len[b] = n_b rows
- * attended (after the append); out is [B, H, d] double.  n_b == 0 gives zeros.
+ * attended (after the append); out is [B, H, d] double.  n_b == 0 or a slot id
+ * outside [0, n_slots) gives zeros.
  */
 void gho_decode_attention(const gho_problem* p, const uint16_t* q,
                           const uint16_t* k_cache, const uint16_t* v_cache,
@@ -191,6 +192,9 @@ void gho_decode_attention(const gho_problem* p, const uint16_t* q,
     double* o = out + it * d;
     for (int64_t j = 0; j < d; ++j) o[j] = 0.0;
     if (n <= 0) continue;
+    /* a context location that does not exist holds no rows: the sequence is skipped, as the
+       append skips it (Section 4.1.3 addresses a sequence by its context location) */
+    if (slot < 0 || slot >= p->n_slots) continue;
     double* s = (double*)malloc((size_t)n * sizeof(double));
     scores(p, q, k_cache, slot, b, h, 0, n, s);
     double mx = s[0];
@@ -222,7 +226,7 @@ void gho_partial(const gho_problem* p, const uint16_t* q,
   const int32_t g = h / G, slot = slot_id[b];
   const int64_t d = p->head_dim;
   for (int64_t j = 0; j < d; ++j) o[j] = 0.0;
-  if (r1 <= r0) {
+  if (r1 <= r0 || slot < 0 || slot >= p->n_slots) {
     *m_out = -INFINITY;
     *l_out = 0.0;
     return;

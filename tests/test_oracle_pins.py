@@ -425,3 +425,22 @@ def test_chunk_of_tokens_sharing_a_slot_is_causal_attention():
         np.testing.assert_allclose(out[:, h], want.numpy(), rtol=1e-12, atol=1e-13)
     # the appended rows are the chunk's keys, in token order
     assert np.array_equal(k.reshape(shape)[1, :, L:L + T], kn.transpose(1, 0, 2))
+
+
+def test_slot_id_out_of_range_gives_zeros_and_leaves_the_others_alone():
+    """A sequence whose context location does not exist is skipped by the attention as it is by
+    the append; the other sequences' results do not change."""
+    rng = np.random.default_rng(404)
+    B, H, Hkv, d, cap, n_slots = 3, 4, 2, 8, 10, 3
+    p = O.make_problem(B, H, Hkv, d, O.BF16, n_slots, cap, 0.3)
+    q = (rng.standard_normal((B, H, d)).astype(np.float32).view(np.uint32) >> 16).astype(np.uint16)
+    kc = (rng.standard_normal((n_slots, Hkv, cap, d)).astype(np.float32).view(np.uint32) >> 16).astype(np.uint16)
+    vc = (rng.standard_normal((n_slots, Hkv, cap, d)).astype(np.float32).view(np.uint32) >> 16).astype(np.uint16)
+    ctx = np.array([5, 7, 3], dtype=np.int32)
+    good = O.decode_attention(p, q, kc, vc, np.array([2, 0, 1], dtype=np.int32), ctx)
+    for bad in (-1, n_slots, 1 << 20):
+        out = O.decode_attention(p, q, kc, vc, np.array([2, bad, 1], dtype=np.int32), ctx)
+        assert not out[1].any()
+        assert np.array_equal(out[[0, 2]], good[[0, 2]])
+        m, l, o = O.partial(p, q, kc, vc, np.array([2, bad, 1], dtype=np.int32), 1, 0, 0, 7)
+        assert m == -np.inf and l == 0.0 and not o.any()
