@@ -16,7 +16,11 @@
  * the rule the prose of Section 4.1.1 and Appendix C describes; with the
  * listing's order the batches of a K > 1 pipeline travel as one clump and the
  * nodes take turns idling, so callers normally pass 1), occupies the pipe for
- * the stage's latency and forwards the event.
+ * the stage's latency and forwards the event.  A pipe's next choice is
+ * scheduled from its state before the chosen batch occupies it (the order of
+ * the updates in the printed algorithms): batches that were already waiting
+ * are committed behind the chosen one at once, in priority order among
+ * themselves, and a batch that arrives while they queue does not overtake them.
  *
  * All times are doubles in the caller's unit.  N must be divisible by K.
  * gen_ts receives E values: the times at which batch 0 wrapped around to the

@@ -61,19 +61,29 @@ typedef struct {
 typedef struct {
   int64_t page_bytes;       /* bytes of one page of one cache                         */
   int64_t virtual_bytes;    /* reserved address range, K plus V                       */
-  int64_t physical_bytes;   /* physical memory owned, K plus V                        */
+  int64_t physical_bytes;   /* the budget in bytes, K plus V (what the pool may own)  */
   int64_t pages_total;      /* physical_pages                                         */
   int64_t pages_mapped;     /* pages currently under some slot                        */
   int32_t slot_capacity;    /* rows per slot after rounding                           */
   int32_t slots_in_use;     /* slots with at least one page                           */
+  int64_t pages_created;    /* physical pages that exist so far (created on demand)   */
 } gh_slot_pool_stats;
 
 /* Status codes are those of gh_tier2.h: 0 ok, -1 null, -2 shape, -3 unsupported
  * (page size not a multiple of the mapping granularity), -5 capacity (the
  * physical budget or a slot's capacity is exceeded), -6 the HIP runtime failed. */
 
-/* Reserves the address range and creates the physical pages (nothing mapped yet). */
+/* Reserves the address range.  Nothing is mapped yet, and no physical page exists yet: pages
+ * are created when a reservation first needs them, up to the budget, and then kept.  The caller's
+ * current device is the same after the call as before. */
 int32_t gh_slot_pool_create(const gh_slot_pool_config* cfg, gh_slot_pool** out);
+
+/* Test aid: a pool with the same bookkeeping and no GPU behind it (no address range, no memory:
+ * gh_slot_pool_k / _v return null).  The fail_at-th page mapping of the pool's life fails
+ * (counted from 0; negative: never), which is how the all-or-nothing rule of gh_slot_pool_reserve
+ * is tested without a device. */
+int32_t gh_slot_pool_create_host_only(const gh_slot_pool_config* cfg, int64_t fail_at,
+                                      gh_slot_pool** out);
 
 /* Unmaps and frees everything.  Work using the pool must have finished. */
 int32_t gh_slot_pool_destroy(gh_slot_pool* pool);
@@ -93,7 +103,9 @@ int32_t gh_slot_pool_blocks(const gh_slot_pool* pool, int32_t* block_rows, int64
  * Makes sure rows [0, rows[i]) of slot slot_id[i] are backed by pages, for
  * i < count.  All or nothing: if the free pages do not cover the whole request,
  * or a row count exceeds the slot capacity, or a slot id is out of range,
- * nothing is mapped and -5 / -2 is returned.  Pages already mapped stay.
+ * nothing is mapped and -5 / -2 is returned; if the runtime refuses a page
+ * midway (-6), what this call had mapped is unmapped again.  Pages mapped by
+ * earlier calls stay.
  */
 int32_t gh_slot_pool_reserve(gh_slot_pool* pool, const int32_t* slot_id,
                              const int32_t* rows, int32_t count);

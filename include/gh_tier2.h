@@ -167,8 +167,10 @@ int32_t gh_decode_num_chunks(const gh_problem* p);
 size_t gh_decode_workspace_bytes(const gh_problem* p);
 
 /*
- * The numbers behind the balanced split, for callers and tests that want to
- * reason about it (host function).  Every strip -- (group, kv head, set of
+ * The numbers behind the balanced split -- how the library parallelises the
+ * attention along the sequence (footnote of Section 2.2) when the lengths of a
+ * batch differ (Section 5.1: prompts of a batch have different lengths) -- for
+ * callers and tests that want to reason about it (host function).  Every strip -- (group, kv head, set of
  * passes_per_strip * waves_per_worker passes of 16 head columns) -- counts ceil(rows / 32) tiles of
  * 32 rows, at least one; the strips are laid end to end in batch order, kv head
  * next, pass set fastest; worker w of n_workers takes tiles [w*share, (w+1)*share)
@@ -220,7 +222,10 @@ int32_t gh_decode_attention(const gh_problem* p, const void* q,
                             void* hip_stream);
 
 /*
- * gh_decode_attention that also finishes what it can.  A head whose rows one
+ * gh_decode_attention that also finishes what it can (footnote of Section 2.2:
+ * the split along the sequence is an option of the attention, not a need -- a
+ * context that is not split has no partial results to merge, and its attention
+ * is Table 5's Q.K, softmax, A.V as they stand).  A head whose rows one
  * wave covers alone (most heads of a large batch) has nothing to merge: its
  * result is normalised and stored straight into `out`, and its record count in
  * the workspace is set to -1, which makes the merges below leave that row of

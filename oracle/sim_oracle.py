@@ -1,20 +1,20 @@
 """Plain-Python reference of the paper's pipeline simulations and in-flight-batch calculus.
 
-TEST INFRASTRUCTURE ONLY (like the rest of oracle/): slow, written step by step in the paper's
-order and notation, imported by tests only.  It shares no code with the C++ simulator of the
-product library.
+TEST INFRASTRUCTURE ONLY (like the rest of oracle/): slow, a direct model of what Appendix C
+describes -- stations that serve one batch at a time, delays, and the rule for choosing the next
+batch -- imported by tests only.  It shares no code with the C++ simulator of the product library.
 
 What it follows:
   * Appendix C, Algorithm 1 (two-tier simulation): every layer has six stages -- Tier-1
     non-attention compute, Tier-1 -> Tier-2 link, half the inter-tier RTT, Tier-2 attention,
-    Tier-2 -> Tier-1 link, half the RTT.  6K pipes (one set of six per Tier-1 node), each a
-    single-consumer queue except the RTT pipes, which are pure delays.  IF batches start in pipe 0;
-    the loop always serves the pipe with the nearest event, pops from it -- among the events that
-    have arrived by then -- the one with the earliest stage, then the earliest timestamp, occupies
-    the pipe for the stage's latency and forwards the event to the pipe of its next stage.  The
-    times at which batch 0 wraps around to stage 0 are returned.
+    Tier-2 -> Tier-1 link, half the RTT.  6K stations (one set of six per Tier-1 node), each
+    serving one batch at a time except the RTT stages, which are pure delays.  IF batches start at
+    the first station; the station whose choice is due first chooses, among the batches that have
+    arrived by then, by stage, then arrival time, then batch id, holds the batch for the stage's
+    latency and passes it on.  The times at which batch 0 comes round to the first stage again are
+    returned.
   * Appendix C, Algorithm 2 (single-tier simulation): the same with three stages per layer
-    (compute, node-to-node link, half the RTT) and 3K pipes.
+    (compute, node-to-node link, half the RTT) and 3K stations.
   * Section 3.2, Eq. 1 (pipeline parallelism), Section 3.3, Eq. 2 (two tiers), Appendix B, Eq. 3
     (tensor parallelism): in-flight batches needed for full utilisation; Section 3.1: the largest
     batch is floor(C_max / (M * IF)).
@@ -22,11 +22,16 @@ What it follows:
     after two warm-up passes, throughput = B * IF / TBT.
 
 Readings where the listing is silent or at odds with the prose:
-  * "pop(.timestamp < next_event_ts[w])" is read as "<=": when a pipe is idle its next event time
-    IS the timestamp of its earliest event, which must be eligible.
-  * stage_to_pipes: layer l lives on Tier-1 node l // (N / K) (N divisible by K), stage s of that
-    layer uses that node's pipe number s mod 6 (or mod 3).
-  * Ties: argmin picks the lowest pipe index; equal (stage, timestamp) pops the lowest batch id.
+  * A batch counts as arrived when its arrival time is at or before the station's decision time
+    (the listing writes a strict comparison; an idle station's decision time IS the arrival time
+    of its earliest batch, which must be eligible).
+  * Layer l lives on Tier-1 node l // (N / K) (N divisible by K); stage s of that layer uses that
+    node's station number s mod 6 (or mod 3).
+  * Ties: the first station in (node, stage) order chooses first; equal (stage, arrival) takes the
+    lowest batch id.
+  * When a station has chosen a batch, its next decision is scheduled from its state before that
+    batch occupies it (the order of the listing's updates), so batches that are already waiting are
+    committed behind it at once; see Station.choose.
   * The listing pops the EARLIEST stage first, while Section 4.1.1 and the prose of Appendix C say
     that batches further along are served first.  Both are implemented.  With the listing's order
     the in-flight batches travel as one clump and the Tier-1 nodes of a K > 1 pipeline take turns
@@ -39,67 +44,92 @@ Readings where the listing is silent or at odds with the prose:
 """
 import math
 
-INF = float("inf")
+NEVER = float("inf")
 
 
-def _simulate(larr, N, K, IF, E, later_first=True):
-    S = len(larr)                      # stages per layer: 6 (two tiers) or 3 (single tier)
+class Station:
+    """One resource of the pipeline: a compute node, a link (one job at a time) or half a round
+    trip (a pure delay: any number of jobs at once, nothing queues).  Jobs wait here as
+    (hop, arrival time, batch) triples, `hop` counting the stages a batch has gone through since
+    the first layer."""
+
+    def __init__(self, latency, one_at_a_time):
+        self.latency = latency
+        self.one_at_a_time = one_at_a_time
+        self.waiting = []
+        self.free_at = 0.0          # when the job in service leaves (stays 0 for a delay)
+        self.decide_at = NEVER      # when the station next chooses a job; NEVER: nothing waits
+
+    def first_arrival(self):
+        return min(job[1] for job in self.waiting) if self.waiting else NEVER
+
+    def accept(self, job):
+        """A job arrives: the choice is due once the station is free and something has arrived."""
+        self.waiting.append(job)
+        self.decide_at = max(self.free_at, self.first_arrival())
+
+    def choose(self, further_along_first):
+        """Takes, among the jobs that have arrived by the decision time, the one furthest along
+        (or least far, with the listing's order), then the earliest arrival, then the lowest
+        batch.  The next choice is scheduled from the station's state BEFORE this job occupies it
+        (Appendix C's listing updates the pipe's next event before it marks the pipe busy): jobs
+        that are already waiting are committed right behind this one, in priority order among
+        themselves, and a job that arrives while they queue does not overtake them."""
+        here = [job for job in self.waiting if job[1] <= self.decide_at]
+        order = (lambda j: (-j[0], j[1], j[2])) if further_along_first else (lambda j: (j[0], j[1], j[2]))
+        job = min(here, key=order)
+        self.waiting.remove(job)
+        self.decide_at = max(self.free_at, self.first_arrival())
+        return job
+
+    def serve(self, arrival):
+        """Departure time of a job that arrived at `arrival`."""
+        if not self.one_at_a_time:
+            return arrival + self.latency
+        self.free_at = max(self.free_at, arrival) + self.latency
+        return self.free_at
+
+
+def _simulate(stage_kinds, N, K, IF, E, later_first=True):
+    """stage_kinds: (latency, one_at_a_time) of the stages of one layer, in order.  Every Tier-1
+    node (N / K consecutive layers) owns one station per stage kind.  Returns E times at which
+    batch 0 entered the last stage of a pass over all N layers."""
+    per_layer = len(stage_kinds)
     assert N % K == 0 and IF >= 1 and E >= 1
-    n_pipes = S * K
-    pipes = [[] for _ in range(n_pipes)]          # lists of (stage, timestamp, id)
     layers_per_node = N // K
+    stations = [Station(lat, serial) for _ in range(K) for lat, serial in stage_kinds]
+    hops_per_pass = per_layer * N
 
-    def stage_to_pipe(stage):
-        layer = stage // S
-        return (layer // layers_per_node) * S + stage % S
+    def station_of(hop):
+        node = (hop // per_layer) // layers_per_node
+        return stations[node * per_layer + hop % per_layer]
 
-    busy_till_ts = [0.0] * n_pipes
-    next_event_ts = [INF] * n_pipes
-    gen_ts = []
-
-    def earliest(pipe):
-        return min(ev[1] for ev in pipe) if pipe else INF
-
-    for i in range(IF):
-        pipes[0].append((0, 0.0, i))
-    next_event_ts[0] = 0.0
-    while len(gen_ts) < E:
-        w = min(range(n_pipes), key=lambda i: next_event_ts[i])
-        assert next_event_ts[w] < INF, "no event left"
-        arrived = [ev for ev in pipes[w] if ev[1] <= next_event_ts[w]]
-        if later_first:
-            ev = min(arrived, key=lambda e: (-e[0], e[1], e[2]))
-        else:
-            ev = min(arrived, key=lambda e: (e[0], e[1], e[2]))
-        pipes[w].remove(ev)
-        stage, timestamp, bid = ev
-        next_event_ts[w] = max(busy_till_ts[w], earliest(pipes[w]))
-
-        delay = larr[stage % S]
-        if stage % 3 != 2:
-            finish_ts = max(busy_till_ts[w], timestamp) + delay
-            busy_till_ts[w] = finish_ts
-        else:
-            finish_ts = timestamp + delay
-        stage = (stage + 1) % (S * N)
-        nw = stage_to_pipe(stage)
-        pipes[nw].append((stage, finish_ts, bid))
-        next_event_ts[nw] = max(busy_till_ts[nw], earliest(pipes[nw]))
-        if stage == 0 and bid == 0:
-            gen_ts.append(timestamp)
-    return gen_ts
+    for batch in range(IF):
+        stations[0].accept((0, 0.0, batch))
+    passes = []
+    while len(passes) < E:
+        st = min(stations, key=lambda s: s.decide_at)        # nearest choice; first station on ties
+        assert st.decide_at < NEVER, "no event left"
+        hop, arrival, batch = st.choose(later_first)
+        leaves = st.serve(arrival)
+        hop = (hop + 1) % hops_per_pass
+        station_of(hop).accept((hop, leaves, batch))
+        if hop == 0 and batch == 0:
+            passes.append(arrival)
+    return passes
 
 
 def two_tier(N, K, IF, E, t_net_12, t_net_21, t_net_rtt, t_c_att, t_c_nonatt, later_first=True):
     """Algorithm 1.  Returns the token generation times of batch 0."""
-    larr = [t_c_nonatt, t_net_12, t_net_rtt / 2, t_c_att, t_net_21, t_net_rtt / 2]
-    return _simulate(larr, N, K, IF, E, later_first)
+    layer = [(t_c_nonatt, True), (t_net_12, True), (t_net_rtt / 2, False),
+             (t_c_att, True), (t_net_21, True), (t_net_rtt / 2, False)]
+    return _simulate(layer, N, K, IF, E, later_first)
 
 
 def single_tier(N, K, IF, E, t_net_link, t_net_rtt, t_c, later_first=True):
     """Algorithm 2.  Returns the token generation times of batch 0."""
-    larr = [t_c, t_net_link, t_net_rtt / 2]
-    return _simulate(larr, N, K, IF, E, later_first)
+    layer = [(t_c, True), (t_net_link, True), (t_net_rtt / 2, False)]
+    return _simulate(layer, N, K, IF, E, later_first)
 
 
 def tbt(gen_ts, warmup=2):

@@ -27,7 +27,7 @@ EXPORTS = ("gh_status_string", "gh_decode_chunk_rows", "gh_decode_num_chunks",
            "gh_decode_attention_static", "gh_decode_step", "gh_decode_step_init")
 GH_OUT_F32, GH_OUT_NATIVE = 0, 1
 GH_PROBE_STORE_PLAIN, GH_PROBE_STORE_NT, GH_PROBE_STORE_WRITE_THROUGH = 0, 1, 2
-POOL_EXPORTS = ("gh_slot_pool_create", "gh_slot_pool_destroy", "gh_slot_pool_k", "gh_slot_pool_v",
+POOL_EXPORTS = ("gh_slot_pool_create", "gh_slot_pool_create_host_only", "gh_slot_pool_destroy", "gh_slot_pool_k", "gh_slot_pool_v",
                 "gh_slot_pool_strides", "gh_slot_pool_reserve", "gh_slot_pool_release",
                 "gh_slot_pool_mapped_rows", "gh_slot_pool_get_stats", "gh_slot_pool_blocks")
 GH_POOL_TOKEN_MAJOR, GH_POOL_HEAD_BLOCKED = 0, 1
@@ -64,7 +64,7 @@ class gh_slot_pool_stats(C.Structure):
     _fields_ = [
         ("page_bytes", C.c_int64), ("virtual_bytes", C.c_int64), ("physical_bytes", C.c_int64),
         ("pages_total", C.c_int64), ("pages_mapped", C.c_int64),
-        ("slot_capacity", C.c_int32), ("slots_in_use", C.c_int32),
+        ("slot_capacity", C.c_int32), ("slots_in_use", C.c_int32), ("pages_created", C.c_int64),
     ]
 
 
@@ -119,6 +119,8 @@ def lib():
         I64P = C.POINTER(C.c_int64)
         L.gh_slot_pool_create.restype = C.c_int32
         L.gh_slot_pool_create.argtypes = [C.POINTER(gh_slot_pool_config), C.POINTER(V)]
+        L.gh_slot_pool_create_host_only.restype = C.c_int32
+        L.gh_slot_pool_create_host_only.argtypes = [C.POINTER(gh_slot_pool_config), C.c_int64, C.POINTER(V)]
         L.gh_slot_pool_destroy.restype = C.c_int32
         L.gh_slot_pool_destroy.argtypes = [V]
         L.gh_slot_pool_k.restype = V
@@ -327,12 +329,16 @@ class SlotPool:
     """Marshalling front end of gh_slot_pool_* (include/gh_slot_pool.h)."""
 
     def __init__(self, n_slots, slot_capacity, n_kv_heads, head_dim, page_rows, physical_pages,
-                 device=0, layout="token_major"):
+                 device=0, layout="token_major", host_only_fail_at=None):
         self._h = C.c_void_p()
         cfg = gh_slot_pool_config(n_slots, slot_capacity, n_kv_heads, head_dim, page_rows, device,
                                   POOL_LAYOUTS[layout], physical_pages)
         self.layout = layout
-        check(lib().gh_slot_pool_create(C.byref(cfg), C.byref(self._h)))
+        if host_only_fail_at is None:
+            check(lib().gh_slot_pool_create(C.byref(cfg), C.byref(self._h)))
+        else:       # bookkeeping only, no GPU (gh_slot_pool_create_host_only)
+            check(lib().gh_slot_pool_create_host_only(C.byref(cfg), int(host_only_fail_at),
+                                                      C.byref(self._h)))
         self.n_slots, self.n_kv_heads, self.head_dim = n_slots, n_kv_heads, head_dim
         self.page_rows = page_rows
         self.capacity = self.stats().slot_capacity

@@ -1,10 +1,12 @@
 // Discrete-event simulation of the single-tier and two-tier pipelines (host code only).
 // Contract and the passages followed: include/gh_sim.h.
 //
-// Data structures differ from a literal reading of the algorithms (which scan every pipe and every
-// queued event at each step): each pipe keeps its queue ordered by arrival time, so that only the
-// events that have already arrived are looked at when choosing what to serve, and the pipes' next
-// event times sit in one ordered set instead of being scanned.
+// The model: every Tier-1 node owns one station per stage kind of a layer.  A station is either a
+// server (a compute node or a link: one batch at a time, the others wait) or a delay (half a round
+// trip: any number of batches at once).  A batch is a job that hops from station to station; the
+// station whose decision is due first chooses among the jobs that have reached it.  Waiting jobs
+// are kept ordered by arrival time, so a decision looks only at the jobs that have arrived, and
+// the stations' decision times sit in one ordered agenda instead of being scanned.
 #include "gh_sim.h"
 
 #include <cmath>
@@ -15,80 +17,99 @@
 
 namespace {
 
-constexpr double kInf = std::numeric_limits<double>::infinity();
+constexpr double kNever = std::numeric_limits<double>::infinity();
 
-struct Event {
-  int32_t stage;
-  double ts;
-  int32_t id;
+struct StageKind {
+  double latency;
+  bool server;        // false: a pure delay
 };
 
-struct Pipe {
-  // (timestamp, stage, id): everything queued, for "earliest timestamp"
-  std::set<std::tuple<double, int32_t, int32_t>> by_time;
-  double busy_till = 0.0;
-  double next_event = kInf;
+struct Job {
+  double arrival;
+  int32_t hop;        // stages gone through since the first layer of the pass
+  int32_t batch;
+  bool operator<(const Job& o) const {
+    return std::tie(arrival, hop, batch) < std::tie(o.arrival, o.hop, o.batch);
+  }
 };
 
-int32_t simulate(const double* larr, int S, int32_t N, int32_t K, int32_t IF, int32_t E,
-                 bool later_first, double* gen_ts) {
-  if (!gen_ts) return -1;
-  if (N <= 0 || K <= 0 || IF <= 0 || E <= 0 || N % K != 0) return -2;
-  const int n_pipes = S * K;
-  const int layers_per_node = N / K;
-  std::vector<Pipe> pipes(n_pipes);
-  std::set<std::pair<double, int>> agenda;          // (next event time, pipe) for finite times
-  auto stage_to_pipe = [&](int32_t stage) {
-    const int layer = stage / S;
-    return (layer / layers_per_node) * S + stage % S;
-  };
-  auto set_next = [&](int w, double t) {
-    Pipe& p = pipes[w];
-    if (p.next_event != kInf) agenda.erase({p.next_event, w});
-    p.next_event = t;
-    if (t != kInf) agenda.insert({t, w});
-  };
-  auto earliest = [&](const Pipe& p) { return p.by_time.empty() ? kInf : std::get<0>(*p.by_time.begin()); };
+class Station {
+ public:
+  StageKind kind{0.0, true};
+  double decide_at = kNever;          // when the next job is chosen; kNever: nothing waits
 
-  for (int32_t i = 0; i < IF; ++i) pipes[0].by_time.insert({0.0, 0, i});
-  set_next(0, 0.0);
-  int32_t logged = 0;
-  while (logged < E) {
-    if (agenda.empty()) return -2;
-    const int w = agenda.begin()->second;            // lowest time, then lowest pipe index
-    Pipe& p = pipes[w];
-    // among the events with timestamp <= next_event: best (stage, timestamp, id) by the rule
-    auto best = p.by_time.end();
-    for (auto it = p.by_time.begin(); it != p.by_time.end() && std::get<0>(*it) <= p.next_event; ++it) {
-      if (best == p.by_time.end()) {
+  double first_arrival() const { return waiting_.empty() ? kNever : waiting_.begin()->arrival; }
+
+  // A job arrives: the decision is due once the station is free and something has arrived.
+  void accept(const Job& j) {
+    waiting_.insert(j);
+    decide_at = std::fmax(free_at_, first_arrival());
+  }
+
+  // Among the jobs that have arrived by the decision time: the one furthest along (or least far),
+  // then the earliest arrival, then the lowest batch.  The next decision is scheduled from the
+  // state before the chosen job occupies the station (see gh_sim.h), i.e. before serve().
+  bool choose(bool further_along_first, Job* out) {
+    auto best = waiting_.end();
+    for (auto it = waiting_.begin(); it != waiting_.end() && it->arrival <= decide_at; ++it) {
+      // within one hop count the set's order (arrival, then batch) already put the right one first
+      if (best == waiting_.end() || (further_along_first ? it->hop > best->hop : it->hop < best->hop))
         best = it;
-        continue;
-      }
-      const int32_t sa = std::get<1>(*it), sb = std::get<1>(*best);
-      const bool better_stage = later_first ? sa > sb : sa < sb;
-      // within one stage the set's order (timestamp, then id) already put the right one first
-      if (better_stage) best = it;
     }
-    if (best == p.by_time.end()) return -2;
-    Event ev{std::get<1>(*best), std::get<0>(*best), std::get<2>(*best)};
-    p.by_time.erase(best);
-    {
-      const double e = earliest(p);
-      set_next(w, e == kInf ? kInf : std::fmax(p.busy_till, e));
-    }
-    const double delay = larr[ev.stage % S];
-    double finish;
-    if (ev.stage % 3 != 2) {
-      finish = std::fmax(p.busy_till, ev.ts) + delay;
-      p.busy_till = finish;
-    } else {
-      finish = ev.ts + delay;
-    }
-    const int32_t stage = (ev.stage + 1) % (S * N);
-    const int nw = stage_to_pipe(stage);
-    pipes[nw].by_time.insert({finish, stage, ev.id});
-    set_next(nw, std::fmax(pipes[nw].busy_till, earliest(pipes[nw])));
-    if (stage == 0 && ev.id == 0) gen_ts[logged++] = ev.ts;
+    if (best == waiting_.end()) return false;
+    *out = *best;
+    waiting_.erase(best);
+    const double next = first_arrival();
+    decide_at = next == kNever ? kNever : std::fmax(free_at_, next);
+    return true;
+  }
+
+  // Departure time of a job that arrived at `arrival`.
+  double serve(double arrival) {
+    if (!kind.server) return arrival + kind.latency;
+    free_at_ = std::fmax(free_at_, arrival) + kind.latency;
+    return free_at_;
+  }
+
+ private:
+  std::set<Job> waiting_;
+  double free_at_ = 0.0;
+};
+
+// kinds: the stages of one layer in order.  passes: E times at which batch 0 entered the last
+// stage of a pass over all N layers.
+int32_t simulate(const std::vector<StageKind>& kinds, int32_t N, int32_t K, int32_t IF, int32_t E,
+                 bool further_along_first, double* passes) {
+  if (!passes) return -1;
+  if (N <= 0 || K <= 0 || IF <= 0 || E <= 0 || N % K != 0) return -2;
+  const int per_layer = (int)kinds.size();
+  const int layers_per_node = N / K;
+  const int32_t hops_per_pass = per_layer * N;
+  std::vector<Station> stations((size_t)per_layer * K);
+  for (size_t i = 0; i < stations.size(); ++i) stations[i].kind = kinds[i % per_layer];
+  std::set<std::pair<double, int>> agenda;            // (decision time, station), finite times only
+  auto station_of = [&](int32_t hop) { return (hop / per_layer) / layers_per_node * per_layer + hop % per_layer; };
+  // runs `change` on station i and keeps the agenda in step with its decision time
+  auto update = [&](int i, auto&& change) {
+    Station& st = stations[i];
+    if (st.decide_at != kNever) agenda.erase({st.decide_at, i});
+    change(st);
+    if (st.decide_at != kNever) agenda.insert({st.decide_at, i});
+  };
+
+  for (int32_t b = 0; b < IF; ++b) update(0, [&](Station& st) { st.accept(Job{0.0, 0, b}); });
+  int32_t done = 0;
+  while (done < E) {
+    if (agenda.empty()) return -2;
+    const int i = agenda.begin()->second;               // earliest decision, first station on ties
+    Job job{};
+    bool chosen = false;
+    update(i, [&](Station& st) { chosen = st.choose(further_along_first, &job); });
+    if (!chosen) return -2;
+    const double leaves = stations[i].serve(job.arrival);
+    const int32_t hop = (job.hop + 1) % hops_per_pass;
+    update(station_of(hop), [&](Station& st) { st.accept(Job{leaves, hop, job.batch}); });
+    if (hop == 0 && job.batch == 0) passes[done++] = job.arrival;
   }
   return 0;
 }
@@ -100,14 +121,15 @@ extern "C" {
 int32_t gh_sim_two_tier(int32_t N, int32_t K, int32_t IF, int32_t E, double t_net_12,
                         double t_net_21, double t_net_rtt, double t_c_att, double t_c_nonatt,
                         int32_t later_first, double* gen_ts) {
-  const double larr[6] = {t_c_nonatt, t_net_12, t_net_rtt / 2, t_c_att, t_net_21, t_net_rtt / 2};
-  return simulate(larr, 6, N, K, IF, E, later_first != 0, gen_ts);
+  return simulate({{t_c_nonatt, true}, {t_net_12, true}, {t_net_rtt / 2, false},
+                   {t_c_att, true}, {t_net_21, true}, {t_net_rtt / 2, false}},
+                  N, K, IF, E, later_first != 0, gen_ts);
 }
 
 int32_t gh_sim_single_tier(int32_t N, int32_t K, int32_t IF, int32_t E, double t_net_link,
                            double t_net_rtt, double t_c, int32_t later_first, double* gen_ts) {
-  const double larr[3] = {t_c, t_net_link, t_net_rtt / 2};
-  return simulate(larr, 3, N, K, IF, E, later_first != 0, gen_ts);
+  return simulate({{t_c, true}, {t_net_link, true}, {t_net_rtt / 2, false}}, N, K, IF, E,
+                  later_first != 0, gen_ts);
 }
 
 double gh_sim_tbt(const double* gen_ts, int32_t E, int32_t warmup) {

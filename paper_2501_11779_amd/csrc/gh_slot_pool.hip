@@ -23,11 +23,46 @@ struct gh_slot_pool {
   std::vector<int32_t> free_list;                                  // ids of unmapped pages
   std::vector<std::vector<int32_t>> slot_pages;                    // per slot, in row order
   int64_t mapped = 0;
+  int64_t created = 0;             // physical pages created so far (on demand, up to the budget)
+  hipMemAllocationProp prop = {};
+  // host-only pools (gh_slot_pool_create_host_only): the bookkeeping with no GPU behind it
+  bool host_only = false;
+  int64_t fail_at = -1, map_calls = 0;
 };
 
 namespace {
 
+// Restores the caller's current device when it goes out of scope.
+struct DeviceGuard {
+  int saved = -1;
+  DeviceGuard() { if (hipGetDevice(&saved) != hipSuccess) saved = -1; }
+  ~DeviceGuard() { if (saved >= 0) (void)hipSetDevice(saved); }
+};
+
+// A physical page for the free list: one already created, or a new one while the budget lasts.
+// Returns its id, or -1.
+int32_t take_page(gh_slot_pool* p) {
+  if (!p->free_list.empty()) {
+    const int32_t page = p->free_list.back();
+    p->free_list.pop_back();
+    return page;
+  }
+  if (p->created >= p->cfg.physical_pages) return -1;
+  if (!p->host_only) {
+    hipMemGenericAllocationHandle_t hk, hv;
+    if (hipMemCreate(&hk, p->page_bytes, &p->prop, 0) != hipSuccess) return -1;
+    if (hipMemCreate(&hv, p->page_bytes, &p->prop, 0) != hipSuccess) {
+      (void)hipMemRelease(hk);
+      return -1;
+    }
+    p->k_pages.push_back(hk);
+    p->v_pages.push_back(hv);
+  }
+  return (int32_t)p->created++;
+}
+
 bool map_page(gh_slot_pool* p, int32_t slot, int32_t index, int32_t page) {
+  if (p->host_only) return p->map_calls++ != p->fail_at;
   const size_t off = (size_t)slot * p->slot_bytes + (size_t)index * p->page_bytes;
   hipMemAccessDesc acc = {};
   acc.location.type = hipMemLocationTypeDevice;
@@ -48,6 +83,7 @@ bool map_page(gh_slot_pool* p, int32_t slot, int32_t index, int32_t page) {
 }
 
 bool unmap_page(gh_slot_pool* p, int32_t slot, int32_t index) {
+  if (p->host_only) return true;
   const size_t off = (size_t)slot * p->slot_bytes + (size_t)index * p->page_bytes;
   const bool a = hipMemUnmap(p->k_va + off, p->page_bytes) == hipSuccess;
   const bool b = hipMemUnmap(p->v_va + off, p->page_bytes) == hipSuccess;
@@ -58,7 +94,8 @@ bool unmap_page(gh_slot_pool* p, int32_t slot, int32_t index) {
 
 extern "C" {
 
-int32_t gh_slot_pool_create(const gh_slot_pool_config* cfg, gh_slot_pool** out) {
+namespace {
+int32_t check_config(const gh_slot_pool_config* cfg, gh_slot_pool** out) {
   if (!cfg || !out) return kNull;
   *out = nullptr;
   if (cfg->n_slots <= 0 || cfg->slot_capacity <= 0 || cfg->n_kv_heads <= 0 || cfg->page_rows <= 0 ||
@@ -69,8 +106,25 @@ int32_t gh_slot_pool_create(const gh_slot_pool_config* cfg, gh_slot_pool** out) 
   if (cfg->layout == GH_POOL_HEAD_BLOCKED &&
       (cfg->page_rows < 32 || (cfg->page_rows & (cfg->page_rows - 1)) != 0))
     return kUnsupported;
+  return kOk;
+}
+void set_geometry(gh_slot_pool* p, const gh_slot_pool_config* cfg) {
+  p->cfg = *cfg;
+  p->page_bytes = (size_t)cfg->page_rows * cfg->n_kv_heads * cfg->head_dim * 2;
+  p->pages_per_slot = (cfg->slot_capacity + cfg->page_rows - 1) / cfg->page_rows;
+  p->capacity = p->pages_per_slot * cfg->page_rows;
+  p->slot_bytes = (size_t)p->pages_per_slot * p->page_bytes;
+  p->range_bytes = (size_t)cfg->n_slots * p->slot_bytes;
+  p->slot_pages.resize(cfg->n_slots);
+}
+}  // namespace
+
+int32_t gh_slot_pool_create(const gh_slot_pool_config* cfg, gh_slot_pool** out) {
+  const int32_t st = check_config(cfg, out);
+  if (st != kOk) return st;
   int n_dev = 0;
   if (hipGetDeviceCount(&n_dev) != hipSuccess || cfg->device >= n_dev) return kHip;
+  DeviceGuard keep_callers_device;
   if (hipSetDevice(cfg->device) != hipSuccess) return kHip;
   int vmm = 0;
   if (hipDeviceGetAttribute(&vmm, hipDeviceAttributeVirtualMemoryManagementSupported, cfg->device) !=
@@ -88,17 +142,12 @@ int32_t gh_slot_pool_create(const gh_slot_pool_config* cfg, gh_slot_pool** out) 
 
   gh_slot_pool* p = new (std::nothrow) gh_slot_pool();
   if (!p) return kHip;
-  p->cfg = *cfg;
-  p->page_bytes = (size_t)cfg->page_rows * cfg->n_kv_heads * cfg->head_dim * 2;
+  set_geometry(p, cfg);
+  p->prop = prop;
   if (p->page_bytes % gran != 0) {
     delete p;
     return kUnsupported;
   }
-  p->pages_per_slot = (cfg->slot_capacity + cfg->page_rows - 1) / cfg->page_rows;
-  p->capacity = p->pages_per_slot * cfg->page_rows;
-  p->slot_bytes = (size_t)p->pages_per_slot * p->page_bytes;
-  p->range_bytes = (size_t)cfg->n_slots * p->slot_bytes;
-
   void* kv = nullptr;
   void* vv = nullptr;
   if (hipMemAddressReserve(&kv, p->range_bytes, gran, nullptr, 0) != hipSuccess) {
@@ -112,28 +161,20 @@ int32_t gh_slot_pool_create(const gh_slot_pool_config* cfg, gh_slot_pool** out) 
   }
   p->k_va = static_cast<char*>(kv);
   p->v_va = static_cast<char*>(vv);
-  p->slot_pages.resize(cfg->n_slots);
-  bool ok = true;
-  for (int64_t i = 0; i < cfg->physical_pages && ok; ++i) {
-    hipMemGenericAllocationHandle_t hk, hv;
-    if (hipMemCreate(&hk, p->page_bytes, &prop, 0) != hipSuccess) {
-      ok = false;
-      break;
-    }
-    if (hipMemCreate(&hv, p->page_bytes, &prop, 0) != hipSuccess) {
-      (void)hipMemRelease(hk);
-      ok = false;
-      break;
-    }
-    p->k_pages.push_back(hk);
-    p->v_pages.push_back(hv);
-  }
-  if (!ok) {
-    gh_slot_pool_destroy(p);
-    return kHip;
-  }
-  p->free_list.reserve(p->k_pages.size());
-  for (int64_t i = (int64_t)p->k_pages.size() - 1; i >= 0; --i) p->free_list.push_back((int32_t)i);
+  // physical pages are created when a reservation first needs them, up to cfg->physical_pages
+  *out = p;
+  return kOk;
+}
+
+int32_t gh_slot_pool_create_host_only(const gh_slot_pool_config* cfg, int64_t fail_at,
+                                      gh_slot_pool** out) {
+  const int32_t st = check_config(cfg, out);
+  if (st != kOk) return st;
+  gh_slot_pool* p = new (std::nothrow) gh_slot_pool();
+  if (!p) return kHip;
+  set_geometry(p, cfg);
+  p->host_only = true;
+  p->fail_at = fail_at;
   *out = p;
   return kOk;
 }
@@ -193,17 +234,33 @@ int32_t gh_slot_pool_reserve(gh_slot_pool* p, const int32_t* slot_id, const int3
     const int32_t have = (int32_t)p->slot_pages[s].size();
     if (want[s] > have) extra += want[s] - have;
   }
-  if (extra > (int64_t)p->free_list.size()) return kCapacity;
-  for (size_t s = 0; s < want.size(); ++s) {
+  if (extra > (int64_t)p->free_list.size() + (p->cfg.physical_pages - p->created)) return kCapacity;
+  // Second pass: map.  If the runtime refuses a page midway, everything this call mapped is taken
+  // back, so that the request either holds in full or has changed nothing.
+  std::vector<int32_t> touched;                                  // slot of every page mapped here
+  bool ok = true;
+  for (size_t s = 0; s < want.size() && ok; ++s) {
     while ((int32_t)p->slot_pages[s].size() < want[s]) {
-      const int32_t page = p->free_list.back();
-      if (!map_page(p, (int32_t)s, (int32_t)p->slot_pages[s].size(), page)) return kHip;
-      p->free_list.pop_back();
+      const int32_t page = take_page(p);
+      if (page < 0 || !map_page(p, (int32_t)s, (int32_t)p->slot_pages[s].size(), page)) {
+        if (page >= 0) p->free_list.push_back(page);
+        ok = false;
+        break;
+      }
       p->slot_pages[s].push_back(page);
+      touched.push_back((int32_t)s);
       ++p->mapped;
     }
   }
-  return kOk;
+  if (ok) return kOk;
+  for (size_t i = touched.size(); i-- > 0;) {
+    auto& pages = p->slot_pages[touched[i]];
+    (void)unmap_page(p, touched[i], (int32_t)pages.size() - 1);
+    p->free_list.push_back(pages.back());
+    pages.pop_back();
+    --p->mapped;
+  }
+  return kHip;
 }
 
 int32_t gh_slot_pool_release(gh_slot_pool* p, const int32_t* slot_id, int32_t count) {
@@ -233,8 +290,9 @@ int32_t gh_slot_pool_get_stats(const gh_slot_pool* p, gh_slot_pool_stats* out) {
   if (!p || !out) return kNull;
   out->page_bytes = (int64_t)p->page_bytes;
   out->virtual_bytes = 2 * (int64_t)p->range_bytes;
-  out->physical_bytes = 2 * (int64_t)p->k_pages.size() * (int64_t)p->page_bytes;
-  out->pages_total = (int64_t)p->k_pages.size();
+  out->physical_bytes = 2 * p->cfg.physical_pages * (int64_t)p->page_bytes;
+  out->pages_total = p->cfg.physical_pages;
+  out->pages_created = p->created;
   out->pages_mapped = p->mapped;
   out->slot_capacity = p->capacity;
   int32_t used = 0;

@@ -326,3 +326,46 @@ def test_attention_out_checks_its_arguments():
     assert G.gh_decode_attention_out(good(batch=0), None, None, None, None, None, None, None,
                                      G.GH_OUT_F32, 0, 0) == G.GH_OK
 
+
+
+# ------------------------------------------------------------------ slot pool bookkeeping, no GPU
+def test_reserve_takes_back_what_it_mapped_when_the_runtime_refuses_a_page():
+    """All or nothing also when the failure comes from the runtime in the middle of a request:
+    a host-only pool whose 5th page mapping fails."""
+    pool = G.SlotPool(6, 1000, 2, 128, 256, physical_pages=12, host_only_fail_at=4)
+    assert pool.k_ptr is None and pool.capacity == 1024
+    assert pool.reserve([0, 1], [512, 300]) == G.GH_OK                    # mappings 0-3
+    assert pool.stats().pages_mapped == 4 and pool.stats().pages_created == 4
+    before = [pool.mapped_rows(s) for s in range(6)]
+    # needs 1 + 3 + 2 more pages; the first of them is the mapping that fails
+    assert pool.reserve([0, 2, 3], [700, 768, 512]) == G.GH_ERR_HIP
+    assert [pool.mapped_rows(s) for s in range(6)] == before
+    st = pool.stats()
+    assert st.pages_mapped == 4 and st.slots_in_use == 2 and st.pages_created == 5
+    # ... and when it fails after some of the request went through (mapping 4 failed above, so
+    # count on: a second pool that fails on its 7th)
+    pool.close()
+    pool = G.SlotPool(6, 1000, 2, 128, 256, physical_pages=12, host_only_fail_at=6)
+    assert pool.reserve([0, 1], [512, 300]) == G.GH_OK                    # mappings 0-3
+    before = [pool.mapped_rows(s) for s in range(6)]
+    assert pool.reserve([0, 2, 3], [700, 768, 512]) == G.GH_ERR_HIP      # 4, 5 succeed, 6 fails
+    assert [pool.mapped_rows(s) for s in range(6)] == before
+    assert pool.stats().pages_mapped == 4
+    # the pages taken back are usable: the same request now goes through (mappings 7-12)
+    assert pool.reserve([0, 2, 3], [700, 768, 512]) == G.GH_OK
+    assert [pool.mapped_rows(s) for s in range(6)] == [768, 512, 768, 512, 0, 0]
+    assert pool.stats().pages_mapped == 10 and pool.stats().pages_created == 10
+    # the budget still binds: 2 pages left, 3 wanted
+    assert pool.reserve([4], [768]) == G.GH_ERR_CAPACITY
+    assert pool.release([0, 1, 2, 3]) == G.GH_OK
+    assert pool.stats().pages_mapped == 0 and pool.stats().pages_created == 10
+    pool.close()
+
+
+def test_host_only_pool_checks_its_configuration_like_the_real_one():
+    with pytest.raises(G.GhError) as e:
+        G.SlotPool(0, 100, 2, 128, 256, 4, host_only_fail_at=-1)
+    assert e.value.status == G.GH_ERR_SHAPE
+    with pytest.raises(G.GhError) as e:
+        G.SlotPool(4, 100, 2, 128, 96, 4, layout="head_blocked", host_only_fail_at=-1)
+    assert e.value.status == G.GH_ERR_UNSUPPORTED

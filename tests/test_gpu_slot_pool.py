@@ -48,6 +48,26 @@ def test_pool_bookkeeping_and_oversubscription():
     pool.close()
 
 
+def test_create_leaves_the_current_device_alone_and_creates_pages_on_demand():
+    import ctypes
+    hip = ctypes.CDLL("libamdhip64.so")
+    dev = ctypes.c_int(-1)
+    assert hip.hipGetDevice(ctypes.byref(dev)) == 0
+    before = dev.value
+    pool = G.SlotPool(n_slots=4, slot_capacity=1000, n_kv_heads=2, head_dim=128, page_rows=256,
+                      physical_pages=1000)                   # a budget far beyond what is used
+    assert hip.hipGetDevice(ctypes.byref(dev)) == 0 and dev.value == before
+    assert torch.cuda.current_device() == before
+    st = pool.stats()
+    assert st.pages_created == 0 and st.pages_total == 1000
+    assert pool.reserve([1], [300]) == G.GH_OK
+    assert pool.stats().pages_created == 2 and pool.stats().pages_mapped == 2
+    assert pool.release([1]) == G.GH_OK
+    assert pool.reserve([2], [100]) == G.GH_OK               # reuses a page that exists
+    assert pool.stats().pages_created == 2
+    pool.close()
+
+
 def test_pool_refuses_bad_configurations():
     with pytest.raises(G.GhError) as e:
         G.SlotPool(0, 100, 2, 128, 256, 4)
