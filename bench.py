@@ -217,7 +217,8 @@ def main():
     ap.add_argument("--steps", type=int, default=50)
     ap.add_argument("--warmup", type=int, default=10)
     ap.add_argument("--workload", default="c4", choices=sorted(CONFIG_OF))
-    ap.add_argument("--kernel", default="auto", choices=["auto", "valu", "mfma"])
+    ap.add_argument("--kernel", default="auto", choices=["auto", "valu", "mfma", "strips"],
+                    help="strips: with --one-launch, a workgroup per strip (GH_KERNEL_STRIPS)")
     ap.add_argument("--chunk-rows", type=int, default=0)
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--batch", type=int, default=0, help="experiment: override the batch size")
@@ -336,7 +337,8 @@ def main():
                       "oversubscription": st.virtual_bytes / st.physical_bytes,
                       "layout": args.paged_layout + ", HIP virtual memory"}
         log(f"paged slots: {paged_info}")
-    kernel = {"auto": G.GH_KERNEL_AUTO, "valu": G.GH_KERNEL_VALU, "mfma": G.GH_KERNEL_MFMA}[args.kernel]
+    kernel = {"auto": G.GH_KERNEL_AUTO, "valu": G.GH_KERNEL_VALU, "mfma": G.GH_KERNEL_MFMA,
+              "strips": G.GH_KERNEL_STRIPS}[args.kernel]
     p = G.problem_from_inputs(inp, chunk_rows=args.chunk_rows, kernel=kernel,
                               tokens_per_group=args.group)
     ws = G.alloc_workspace(p)

@@ -89,7 +89,15 @@ typedef enum { GH_F16 = 0, GH_BF16 = 1 } gh_dtype;
 typedef enum {
   GH_KERNEL_AUTO = 0, /* the library's measured choice (currently always MFMA)   */
   GH_KERNEL_VALU = 1, /* fp32 vector arithmetic, passes of up to 8 heads          */
-  GH_KERNEL_MFMA = 2  /* matrix-core tiles, passes of up to 16 heads, two at once  */
+  GH_KERNEL_MFMA = 2, /* matrix-core tiles, passes of up to 16 heads, two at once  */
+  GH_KERNEL_STRIPS = 3 /* gh_decode_step only (elsewhere: GH_KERNEL_AUTO): the same
+                          tiles with one workgroup per (sequence, kv head) strip,
+                          its four waves merged on chip -- no workspace traffic, no
+                          partial records.  For batches of up to about a hundred
+                          sequences whose contexts have about the same length (the
+                          regime Appendix C profiles the attention in); with very
+                          uneven lengths the longest strips finish alone and the
+                          library's equal shares are the better split.           */
 } gh_kernel;
 
 /* Bits OR-ed into *dev_status by gh_kv_append. */
@@ -290,6 +298,8 @@ int32_t gh_decode_reduce_native(const gh_problem* p, const void* workspace,
  *     written.  Deterministic for given inputs (fixed summation order).
  *   - With a fixed split (chunk_rows > 0), GH_KERNEL_VALU or a batch beyond the
  *     balanced split the call issues the three kernels instead, same result.
+ *   - kernel = GH_KERNEL_STRIPS (with chunk_rows = 0): one workgroup per strip,
+ *     see gh_kernel; the workspace is then not touched.
  */
 int32_t gh_decode_step_init(const gh_problem* p, void* workspace, size_t workspace_bytes,
                             void* hip_stream);

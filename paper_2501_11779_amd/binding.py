@@ -18,7 +18,7 @@ GH_ERR_NULL, GH_ERR_SHAPE, GH_ERR_UNSUPPORTED = -1, -2, -3
 GH_ERR_WORKSPACE, GH_ERR_CAPACITY, GH_ERR_HIP, GH_ERR_SCRATCH = -4, -5, -6, -7
 GH_STATIC_SCRATCH_BYTES = 64 << 20
 GH_F16, GH_BF16 = 0, 1
-GH_KERNEL_AUTO, GH_KERNEL_VALU, GH_KERNEL_MFMA = 0, 1, 2
+GH_KERNEL_AUTO, GH_KERNEL_VALU, GH_KERNEL_MFMA, GH_KERNEL_STRIPS = 0, 1, 2, 3
 GH_DEV_BAD_SLOT, GH_DEV_BAD_POS = 1, 2
 
 EXPORTS = ("gh_status_string", "gh_decode_chunk_rows", "gh_decode_num_chunks",

@@ -1063,4 +1063,147 @@ __global__ __launch_bounds__(256, P == 1 ? 2 : 1) void attn_mfma_balanced_kernel
   }
 }
 
+// The one-launch step for SMALL batches: one workgroup per strip (sequence, kv head, head pass).
+//
+// When a batch has fewer strips than the chip has wave slots, cutting the strips into equal shares
+// (above) leaves every strip in pieces on different compute units, and putting the pieces together
+// costs memory round trips that are as long as the streaming itself.  Here the WAVES waves of one
+// workgroup take a strip's tiles in turn (wave w: tiles w, w + WAVES, ...), keep their own running
+// sums, and merge them through LDS: no workspace, no counters, no second kernel.  The appended row
+// is the strip's last tile, loaded from k_new / v_new and written to the caches from registers, as
+// in the balanced one-launch kernel.  ctx_len[] holds the positions of the new rows.
+//
+// LDS: WAVES x 16 head columns x (128 + 4) floats of scaled partial rows, and the (exponent, sum)
+// pairs: 68 KB for eight waves.
+template <bool BF16, int WAVES>
+__global__ __launch_bounds__(WAVES * 64, 2) void attn_mfma_strip_kernel(const AttnArgs a) {
+  constexpr int kPitch = kHeadDim + 4;                         // floats per head column in LDS
+  __shared__ float rows_lds[WAVES][16][kPitch];
+  __shared__ float m_lds[WAVES][16], l_lds[WAVES][16];
+  auto uni = [](int x) { return __builtin_amdgcn_readfirstlane(x); };
+  const int tid = threadIdx.x, lane = tid & 63, wave = uni(tid >> 6);
+  const int hn = lane & 15, c = lane >> 4;
+
+  // strip of this workgroup: pass fastest, then kv head, then sequence
+  int rest = (int)blockIdx.x;
+  const int pass = rest % a.n_pass;
+  rest /= a.n_pass;
+  const int g = rest % a.n_kv_heads, b = rest / a.n_kv_heads;
+  const int left = a.group - pass * a.heads_per_pass;
+  const int nh = left < a.heads_per_pass ? left : a.heads_per_pass;
+
+  const int slot = uni(a.slot_id[b]), pos = uni(a.ctx_len[b]);
+  const bool bad_slot = slot < 0 || slot >= a.n_slots, bad_pos = pos < 0 || pos >= a.row_limit;
+  if ((bad_slot || bad_pos) && a.dev_status && g == 0 && pass == 0 && tid == 0)
+    atomicOr(a.dev_status, (bad_slot ? 1 : 0) | (bad_pos ? 2 : 0));
+  const int n = bad_slot || bad_pos ? 0 : pos + 1;             // rows attended; row n - 1 is the new one
+  const int tiles = n > 0 ? ((n - 1 + 31) >> 5) + 1 : 0;       // cached rows in tiles, then the new row
+
+  u32x4 qop[1][4];
+  {
+    u32x4 qraw[4];
+    load_q(qraw, a, b, g, pass, nh, hn, c);
+    keep_real_heads(qop[0], qraw, nh, hn);
+  }
+  f32x4 acc[1][8];
+#pragma unroll
+  for (int tcol = 0; tcol < 8; ++tcol) acc[0][tcol] = f32x4{0.f, 0.f, 0.f, 0.f};
+  float m[1] = {kNegInf}, l[1] = {0.f};
+
+  const LaneGeom lg = lane_geom(hn, c);
+  const uint32_t row_bytes = (uint32_t)a.row_stride * 2u;
+  const int64_t strip = (int64_t)(n > 0 ? slot : 0) * a.slot_stride + (int64_t)g * a.head_stride;
+  const int64_t from = (int64_t)b * a.new_batch_stride + (int64_t)g * kHeadDim;
+  // tile t of the strip; past this wave's last one the same tile is loaded again (from cache), so
+  // that every wait count is exact
+  auto issue = [&](TileRegs& regs, int t) {
+    if (t + 1 == tiles) {
+      load_tile<true>(regs, reinterpret_cast<const char*>(a.k_new + from),
+                      reinterpret_cast<const char*>(a.v_new + from), row_bytes, 1, lg);
+    } else {
+      const int64_t at = strip + row_offset(t * 32, a.row_stride, a.block_stride, a.block_shift, a.block_mask);
+      load_tile<true>(regs, reinterpret_cast<const char*>(a.k_cache + at),
+                      reinterpret_cast<const char*>(a.v_cache + at), row_bytes, n - 1 - t * 32, lg);
+    }
+  };
+  auto compute = [&](const TileRegs& regs, int t) {
+    const bool last = t + 1 == tiles;
+    const int upto[1] = {last ? n : n - 1};
+    process_tile<BF16, 1>(regs, qop, acc, m, l, a.scale_log2e, last ? n - 1 : t * 32, upto, c);
+    if (last && pass == 0) {                                   // the append, from the tile's registers
+      const int64_t at = strip + row_offset(n - 1, a.row_stride, a.block_stride, a.block_shift, a.block_mask);
+      store_new_row(regs, reinterpret_cast<char*>(const_cast<uint16_t*>(a.k_cache) + at),
+                    reinterpret_cast<char*>(const_cast<uint16_t*>(a.v_cache) + at), 0, lg);
+    }
+  };
+  if (wave < tiles) {
+    // this wave's tiles: wave, wave + WAVES, ...; two register tiles, one in flight
+    const int last_mine = wave + (tiles - 1 - wave) / WAVES * WAVES;
+    TileRegs ta, tb;
+    issue(ta, wave);
+    for (int t = wave;; t += 2 * WAVES) {
+      issue(tb, t + WAVES <= last_mine ? t + WAVES : last_mine);
+      compute(ta, t);
+      if (t + WAVES > last_mine) break;
+      issue(ta, t + 2 * WAVES <= last_mine ? t + 2 * WAVES : last_mine);
+      compute(tb, t + WAVES);
+      if (t + 2 * WAVES > last_mine) break;
+    }
+  }
+
+  // merge through LDS: common exponent per head column, every wave's rows scaled to it
+  l[0] = rows_sum(l[0]);
+  if (c == 0) {
+    m_lds[wave][hn] = m[0];
+    l_lds[wave][hn] = l[0];
+  }
+  __syncthreads();
+  float top = kNegInf;
+#pragma unroll
+  for (int w = 0; w < WAVES; ++w) top = fmaxf(top, l_lds[w][hn] > 0.f ? m_lds[w][hn] : kNegInf);
+  const float mine = l[0] > 0.f && top != kNegInf ? fast_exp2(m[0] - top) : 0.f;
+#pragma unroll
+  for (int i = 0; i < 4; ++i) {
+    // register i of column tile t is column 32c + 8i + t: eight consecutive columns per i
+    f32x4 lo = {acc[0][0][i], acc[0][1][i], acc[0][2][i], acc[0][3][i]};
+    f32x4 hi = {acc[0][4][i], acc[0][5][i], acc[0][6][i], acc[0][7][i]};
+#pragma unroll
+    for (int e = 0; e < 4; ++e) {
+      lo[e] = mine > 0.f ? lo[e] * mine : 0.f;                 // (a wave without rows holds zeros)
+      hi[e] = mine > 0.f ? hi[e] * mine : 0.f;
+    }
+    *reinterpret_cast<f32x4*>(&rows_lds[wave][hn][32 * c + 8 * i]) = lo;
+    *reinterpret_cast<f32x4*>(&rows_lds[wave][hn][32 * c + 8 * i + 4]) = hi;
+  }
+  __syncthreads();
+  // thread -> (head column, four output columns); WAVES * 64 threads cover 16 x 32 such pieces
+  typedef uint32_t u32x2 __attribute__((ext_vector_type(2)));
+  for (int piece = tid; piece < 16 * 32; piece += WAVES * 64) {
+    const int head = piece >> 5, col = (piece & 31) * 4;
+    if (head >= nh) continue;
+    float peak = kNegInf;
+#pragma unroll
+    for (int w = 0; w < WAVES; ++w) peak = fmaxf(peak, l_lds[w][head] > 0.f ? m_lds[w][head] : kNegInf);
+    float total = 0.f;
+    f32x4 x = {0.f, 0.f, 0.f, 0.f};
+#pragma unroll
+    for (int w = 0; w < WAVES; ++w) {
+      const float lw = l_lds[w][head];
+      if (lw > 0.f) {
+        total = fmaf(fast_exp2(m_lds[w][head] - peak), lw, total);
+        x += *reinterpret_cast<const f32x4*>(&rows_lds[w][head][col]);
+      }
+    }
+#pragma unroll
+    for (int e = 0; e < 4; ++e) x[e] = total > 0.f ? x[e] / total : 0.f;
+    const int64_t row = column_index(a, b, g, pass, head);
+    if (a.out_kind == 1) {
+      *reinterpret_cast<f32x4*>(static_cast<float*>(a.out) + row * kHeadDim + col) = x;
+    } else {
+      const u32x2 w2 = {pack2<BF16>(x[0], x[1]), pack2<BF16>(x[2], x[3])};
+      *reinterpret_cast<u32x2*>(static_cast<uint16_t*>(a.out) + row * kHeadDim + col) = w2;
+    }
+  }
+}
+
 }  // namespace gh

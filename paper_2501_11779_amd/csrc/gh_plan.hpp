@@ -48,7 +48,8 @@ inline int32_t check_problem(const gh_problem* p) {
   if (p->n_q_heads % p->n_kv_heads != 0) return GH_ERR_SHAPE;
   if (p->head_dim != kHeadDim) return GH_ERR_UNSUPPORTED;
   if (p->dtype != GH_F16 && p->dtype != GH_BF16) return GH_ERR_UNSUPPORTED;
-  if (p->kernel != GH_KERNEL_AUTO && p->kernel != GH_KERNEL_VALU && p->kernel != GH_KERNEL_MFMA)
+  if (p->kernel != GH_KERNEL_AUTO && p->kernel != GH_KERNEL_VALU && p->kernel != GH_KERNEL_MFMA &&
+      p->kernel != GH_KERNEL_STRIPS)
     return GH_ERR_UNSUPPORTED;
   if (p->row_stride < p->head_dim || p->head_stride <= 0 || p->slot_stride <= 0) return GH_ERR_SHAPE;
   if (p->row_stride % 8 || p->head_stride % 8 || p->slot_stride % 8) return GH_ERR_UNSUPPORTED;
@@ -80,7 +81,8 @@ inline int32_t check_problem(const gh_problem* p) {
 inline int resolve_kernel(const gh_problem* p) {
   // Measured on MI355X: the matrix-core kernel is faster for every head-group size, plain
   // multi-head attention included (81% against 68% of peak HBM bandwidth at group size 1).
-  return p->kernel != GH_KERNEL_AUTO ? p->kernel : GH_KERNEL_MFMA;
+  // (GH_KERNEL_STRIPS only changes gh_decode_step; everywhere else it is the matrix-core kernel)
+  return p->kernel == GH_KERNEL_VALU ? GH_KERNEL_VALU : GH_KERNEL_MFMA;
 }
 
 // Heads of one kv head handled by a single work item, and how many such passes.

@@ -171,6 +171,68 @@ def test_the_three_kernel_route_of_the_step_call_gives_the_same(how):
     assert np.array_equal(W.bits(inp["v_cache"]), host["v_cache"])
 
 
+@pytest.mark.parametrize("dtype", ["f16", "bf16"])
+@pytest.mark.parametrize("H,Hkv", [(4, 4), (8, 1), (6, 2), (40, 2)])
+def test_step_with_a_workgroup_per_strip(H, Hkv, dtype):
+    """GH_KERNEL_STRIPS: the four waves of a workgroup share a strip and merge on chip.  Same
+    contract, no workspace traffic: the workspace (never initialised here) stays as it was."""
+    w = W.Workload("strips", len(RAGGED), H, Hkv, 128, dtype, ("const", 0), 170 + H + Hkv)
+    inp = W.make_inputs(w, DEV, lengths=RAGGED, n_slots=len(RAGGED) + 3)
+    host = Hh.host_copy(inp)
+    p = G.problem_from_inputs(inp, kernel=G.GH_KERNEL_STRIPS)
+    ws = G.alloc_workspace(p, DEV)
+    ws.view(torch.int32).fill_(0x7fc00123)                   # NaN patterns, counters included
+    for out_dtype in (torch.float32, W.TORCH_DTYPE[dtype]):
+        out = torch.full((w.batch, H, 128), float("nan"), dtype=out_dtype, device=DEV)
+        G.decode_step_one_launch(p, inp, ws, out)
+        torch.cuda.synchronize()
+        if out_dtype == torch.float32:
+            want = Hh.oracle_step(inp, host)
+            Hh.assert_tight(out.cpu().numpy(), want, f"strips {dtype} H={H}/{Hkv}")
+            assert np.array_equal(W.bits(inp["k_cache"]), host["k_cache"])
+            assert np.array_equal(W.bits(inp["v_cache"]), host["v_cache"])
+        else:
+            assert Hh.assert_rounded_within(W.bits(out), want, dtype, Hh.TIGHT_MAX_ABS, "strips 16-bit") > 0.995
+    assert (ws.view(torch.int32) == 0x7fc00123).all()
+
+
+def test_strips_step_flags_bad_entries_and_handles_layouts_and_a_decode_loop():
+    lengths = np.array([100, 40, 7, 300, 64, 0, 31], dtype=np.int32)
+    w = W.Workload("stripsbad", 7, 16, 2, 128, "bf16", ("const", 0), 171)
+    for layout in ("head_major", "token_major", "head_blocked"):
+        inp = W.make_inputs(w, DEV, lengths=lengths, n_slots=9, capacity=320, layout=layout, block_rows=64)
+        host = Hh.host_copy(inp)
+        p = G.problem_from_inputs(inp, kernel=G.GH_KERNEL_STRIPS, max_ctx_len=320)
+        ws = G.alloc_workspace(p, DEV)
+        out = torch.full((7, 16, 128), float("nan"), dtype=torch.float32, device=DEV)
+        gen = torch.Generator(device=DEV)
+        gen.manual_seed(3)
+        for t in range(3):                                   # three tokens, positions advancing
+            pos = lengths + t
+            for name in ("q", "k_new", "v_new"):
+                inp[name] = torch.randn(inp[name].shape, generator=gen, device=DEV).to(inp[name].dtype)
+                host[name] = W.bits(inp[name])
+            inp["pos"] = torch.from_numpy(pos.copy()).to(DEV)
+            host["pos"], host["ctx_len"] = pos.copy(), (pos + 1).astype(np.int32)
+            G.decode_step_one_launch(p, inp, ws, out)
+            torch.cuda.synchronize()
+            Hh.assert_tight(out.cpu().numpy(), Hh.oracle_step(inp, host), f"{layout} token {t}")
+            assert np.array_equal(W.bits(inp["k_cache"]), host["k_cache"])
+            assert np.array_equal(W.bits(inp["v_cache"]), host["v_cache"])
+    # a slot that does not exist, a position beyond the slot
+    inp["slot_id"][1] = 17
+    inp["pos"][3] = 320
+    status = torch.zeros(1, dtype=torch.int32, device=DEV)
+    before_k = W.bits(inp["k_cache"])
+    G.decode_step_one_launch(p, inp, ws, out, dev_status=status)
+    torch.cuda.synchronize()
+    got = out.cpu().numpy()
+    assert int(status.item()) == (G.GH_DEV_BAD_SLOT | G.GH_DEV_BAD_POS)
+    assert not got[1].any() and not got[3].any() and np.isfinite(got).all()
+    changed = (W.bits(inp["k_cache"]) != before_k)
+    assert not changed[int(host["slot_id"][3])].any()        # nothing appended for the bad position
+
+
 def test_one_launch_step_is_bit_reproducible():
     w = W.Workload("steprep", 50, 16, 2, 128, "bf16", ("uniform", 0, 3000), 166)
     inp = W.make_inputs(w, DEV)
