@@ -1,5 +1,6 @@
 """Measure the Tier-2 curve the configuration search needs: time of one layer's attention step
-(gh_kv_append + gh_decode_attention + gh_decode_reduce) against batch size, every context at the
+(the fastest of gh_kv_append + gh_decode_attention + gh_decode_reduce, gh_decode_step, and
+gh_decode_step with a workgroup per strip) against batch size, every context at the
 maximum sequence length (Appendix C: kernels are profiled at batch sizes about sqrt(2) apart and
 the attention time is taken at full sequence length).  Needs an MI355X.
 
@@ -35,33 +36,50 @@ def main():
     S, H, Hkv, Bmax = args.seq_len, args.heads, args.kv_heads, args.max_batch
     w = W.Workload("profile", Bmax, H, Hkv, 128, args.dtype, ("const", S - 1), 4242)
     inp = W.make_inputs(w, "cuda", poison=False)
-    batches, seconds = [], []
+    batches, seconds, how = [], [], []
+    per_variant = {"three_launches": [], "one_launch": [], "one_launch_strips": []}
     for B in profile_batch_sizes(Bmax):
-        p = G.make_problem(B, H, Hkv, 128, G.GH_BF16 if args.dtype == "bf16" else G.GH_F16,
-                           inp["n_slots"], inp["capacity"], S, inp["strides"], inp["scale"])
-        ws = G.alloc_workspace(p)
-        out = torch.empty((B, H, 128), dtype=torch.float32, device="cuda")
+        dt = G.GH_BF16 if args.dtype == "bf16" else G.GH_F16
         sub = dict(inp)
         for key in ("q", "k_new", "v_new", "slot_id", "pos", "ctx_len"):
             sub[key] = inp[key][:B].contiguous()
-        for _ in range(3):
-            G.decode_step(p, sub, ws, out)
-        torch.cuda.synchronize()
-        times = []
-        for _ in range(args.repeats):
-            e0, e1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
-            e0.record()
-            G.decode_step(p, sub, ws, out)
-            e1.record()
+        out = torch.empty((B, H, 128), dtype=torch.float32, device="cuda")
+
+        def timed(run):
+            for _ in range(3):
+                run()
             torch.cuda.synchronize()
-            times.append(e0.elapsed_time(e1) * 1e-3)
-        t = float(np.median(times))
+            times = []
+            for _ in range(args.repeats):
+                e0, e1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+                e0.record()
+                run()
+                e1.record()
+                torch.cuda.synchronize()
+                times.append(e0.elapsed_time(e1) * 1e-3)
+            return float(np.median(times))
+
+        # the step three ways: the three calls, one launch with the library's split, and one launch
+        # with a workgroup per strip (every context has the same length here, its best case)
+        p = G.make_problem(B, H, Hkv, 128, dt, inp["n_slots"], inp["capacity"], S, inp["strides"],
+                           inp["scale"])
+        ws = G.alloc_step_workspace(p)
+        t3 = timed(lambda: G.decode_step(p, sub, ws, out))
+        t1 = timed(lambda: G.decode_step_one_launch(p, sub, ws, out))
+        ps = G.make_problem(B, H, Hkv, 128, dt, inp["n_slots"], inp["capacity"], S, inp["strides"],
+                            inp["scale"], kernel=G.GH_KERNEL_STRIPS)
+        ts = timed(lambda: G.decode_step_one_launch(ps, sub, ws, out))
+        for name, t in (("three_launches", t3), ("one_launch", t1), ("one_launch_strips", ts)):
+            per_variant[name].append(t)
+        t, name = min((t3, "three_launches"), (t1, "one_launch"), (ts, "one_launch_strips"))
         batches.append(B)
         seconds.append(t)
-        print(f"B={B:5d}  {t * 1e6:9.1f} us  {B / t:12.0f} sequence-steps/s", file=sys.stderr, flush=True)
+        how.append(name)
+        print(f"B={B:5d}  three launches {t3 * 1e6:8.1f} us  one launch {t1 * 1e6:8.1f} us  strips "
+              f"{ts * 1e6:8.1f} us  -> {B / t:12.0f} sequence-steps/s ({name})", file=sys.stderr, flush=True)
     doc = {"what": "one layer's attention step on one MI355X, every context at seq_len rows",
            "seq_len": S, "n_q_heads": H, "n_kv_heads": Hkv, "head_dim": 128, "dtype": args.dtype,
-           "batch": batches, "seconds": seconds}
+           "batch": batches, "seconds": seconds, "fastest": how, "seconds_by_variant": per_variant}
     with open(args.out, "w") as f:
         json.dump(doc, f, indent=1)
     print(args.out)
