@@ -1,7 +1,7 @@
 """Profile one benchmark configuration with rocprofv3 and write its summary.
 
     python -m paper_2501_11779_amd.rocprof_summary --workload c4 [--sq] [--tag NAME]
-                                                   [--bench-args "--paged ..."] [--out DIR]
+                                                   [--bench-args="--paged ..."] [--out DIR]
     python -m paper_2501_11779_amd.rocprof_summary --ceiling [--out DIR]
 
 Runs, each as its own rocprofv3 process around `python3 bench.py ...` (counters never share a run
@@ -79,7 +79,7 @@ def summarise_workload(args, work):
     out = [f"# rocprofv3 summary: Tier-2 attention step, workload {tag} ({CONFIG_OF[wl]}"
            f"{', ' + args.bench_args if args.bench_args else ''}), MI355X (gfx950)\n",
            "Written by `python -m paper_2501_11779_amd.rocprof_summary --workload " + wl
-           + (f' --tag {tag} --bench-args "{args.bench_args}"' if args.bench_args else "")
+           + (f' --tag {tag} --bench-args="{args.bench_args}"' if args.bench_args else "")
            + (" --sq" if args.sq else "") + "`, which ran (from /tmp, `TMPDIR=/tmp`, `$R` = "
            "repository root):\n"]
     kt, log, c1 = rocprof(work, f"kt_{tag}", ["--kernel-trace", "--stats"],
