@@ -349,6 +349,13 @@ def main():
     step_bytes = W.algorithmic_bytes(w, ctx)
     attn_bytes = W.attention_bytes(w, ctx)
     flops = W.algorithmic_flops(w, ctx)
+    if args.group > 1:
+        # a declared group streams its slot once (the rows of its longest token): K/V rows count
+        # once per group, q once per entry
+        row_bytes = 2 * w.n_kv_heads * w.head_dim * W.ELEM_BYTES
+        saved = int((ctx.sum() - ctx.reshape(-1, args.group).max(axis=1).sum()) * row_bytes)
+        attn_bytes -= saved
+        step_bytes -= saved
     chunk_rows, n_chunks = G.gh_decode_chunk_rows(p), G.gh_decode_num_chunks(p)
     log(f"workload {w.name}: B={w.batch} H={w.n_q_heads}/{w.n_kv_heads} d={w.head_dim} {w.dtype} "
         f"sum(n_b)={int(ctx.sum())} step_bytes={step_bytes / 1e9:.3f} GB "

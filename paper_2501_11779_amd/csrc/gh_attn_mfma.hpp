@@ -849,11 +849,14 @@ __global__ __launch_bounds__(256, P == 1 ? 2 : 1) void attn_mfma_balanced_kernel
   int lim[P], nh[P], qnext_nh[P];
   int g, pass0;                       // kv head and first pass of the strip being computed
   int qg = 0, qpass0 = 0, lnext_slot = 0;   // ... and of the strip whose rows are in flight
-  // Q rows and limits of the P passes of a strip; a pass without columns fetches the first's
+  // Q rows and limits of the P passes of a strip.  A pass without columns fetches those of pass 0,
+  // which always has some (the wave's own first pass may be beyond the group's columns too, when
+  // the waves of a worker carry more passes than the group has: its columns would belong to token
+  // rows or heads that do not exist, past the end of q for the last sequence).
   auto fetch = [&](const TileCursor& cu, int b, int fg, int fpass0, const int (&fnh)[P]) {
 #pragma unroll
     for (int i = 0; i < P; ++i) {
-      const int pass = fnh[i] > 0 ? fpass0 + i : fpass0;
+      const int pass = fnh[i] > 0 ? fpass0 + i : 0;
       load_q(qnext[i], a, b, fg, pass, fnh[i], hn, c);
       lnext[i] = load_limit(cu, b, fg, pass, fnh[i]);
     }
@@ -992,8 +995,8 @@ __global__ __launch_bounds__(256, P == 1 ? 2 : 1) void attn_mfma_balanced_kernel
           } else {
 #pragma unroll
             for (int i = 0; i < P; ++i) {
-              // (a pass without columns fetches the first pass's rows, as fetch() does)
-              load_q(qnext[i], a, qb, qg, qnext_nh[i] > 0 ? qpass0 + i : qpass0, qnext_nh[i], hn, c);
+              // (a pass without columns fetches pass 0's rows, as fetch() does)
+              load_q(qnext[i], a, qb, qg, qnext_nh[i] > 0 ? qpass0 + i : 0, qnext_nh[i], hn, c);
               lnext[i] = Limit{0, more ? qs.n : cp.n};
             }
           }

@@ -86,7 +86,8 @@ RAGGED = np.array([0, 1, 30, 31, 32, 62, 63, 64, 65, 127, 128, 191, 299, 512, 70
 @pytest.mark.parametrize("kernel", ["valu", "mfma"])
 @pytest.mark.parametrize("dtype", ["f16", "bf16"])
 @pytest.mark.parametrize("H,Hkv", [(4, 4), (4, 2), (8, 2), (8, 1), (6, 2), (32, 2), (40, 2),
-                                  (40, 1)])   # 40 heads on one kv head: three passes, the last strip half empty
+                                  (40, 1),    # 40 heads on one kv head: three passes, the last strip half empty
+                                  (72, 1)])   # five passes: the fourth wave of the worker carries no column
 @pytest.mark.parametrize("chunk_rows", [64, 192, 0])
 def test_attention_matches_oracle_on_ragged_batch(kernel, dtype, H, Hkv, chunk_rows):
     w = small("rag", len(RAGGED), H, Hkv, dtype, 40 + H + Hkv)
@@ -336,6 +337,7 @@ def _grouped_rows(T):
                                      (6, 2, 5), (2, 2, 40),
                                      (8, 2, 12),     # 48 columns: two waves on one stream
                                      (16, 2, 16),    # 128 columns: four waves on one stream
+                                     (10, 2, 16),    # 80 columns: five passes, the fourth wave has none
                                      (8, 1, 64)])    # 512 columns: four such strips
 def test_token_groups_share_the_slot_stream_and_match_the_oracle(H, Hkv, T, dtype):
     """tokens_per_group = T: the T rows of a group are head columns of the same tiles, each masked

@@ -45,7 +45,7 @@ def run_step(inp, chunk_rows=0, kernel=G.GH_KERNEL_AUTO, dtype=torch.float32, st
 
 
 @pytest.mark.parametrize("dtype", ["f16", "bf16"])
-@pytest.mark.parametrize("H,Hkv", [(4, 4), (8, 2), (8, 1), (6, 2), (32, 2), (40, 2), (40, 1)])
+@pytest.mark.parametrize("H,Hkv", [(4, 4), (8, 2), (8, 1), (6, 2), (32, 2), (40, 2), (40, 1), (72, 1)])
 def test_one_launch_step_matches_oracle_on_ragged_batch(H, Hkv, dtype):
     w = W.Workload("step", len(RAGGED), H, Hkv, 128, dtype, ("const", 0), 140 + H + Hkv)
     inp = W.make_inputs(w, DEV, lengths=RAGGED, n_slots=len(RAGGED) + 3)
