@@ -114,9 +114,11 @@ def one_thread_oracle(names=("c1", "c2")):
     return out
 
 
-def time_default_step(name, steps, warmup):
+def time_default_step(name, steps, warmup, keep):
     """Append + attention + merge of workload `name` in the library's default launch, timed like
-    the headline workload (wall clock for the step, HIP events on the launch stream per kernel)."""
+    the headline workload (wall clock for the step, HIP events on the launch stream per kernel).
+    The tensors are appended to `keep`: a later workload placed in memory that an earlier one gave
+    back runs 2-3% slower than in memory the process takes for the first time."""
     import numpy as np
     import torch
     from paper_2501_11779_amd import binding as G
@@ -127,6 +129,7 @@ def time_default_step(name, steps, warmup):
     p = G.problem_from_inputs(inp)
     ws = G.alloc_workspace(p)
     out = torch.empty((w.batch, w.n_q_heads, w.head_dim), device="cuda", dtype=torch.float32)
+    keep.append((inp, ws, out))
     ctx = inp["lengths"].astype(np.int64) + 1
     attn_bytes = W.attention_bytes(w, ctx)
 
@@ -486,12 +489,11 @@ def main():
     if plain and w.name == "c4" and not args.no_other_workloads:
         # the other full-size workloads of the target, each for a few steps in the same launch
         # configuration, so that one run's record covers them all
-        del inp, ws, out
-        if pool is not None:
-            pool.close()
-        torch.cuda.empty_cache()
+        # (the headline workload's tensors stay allocated: memory handed back to the driver and
+        # taken again comes in smaller physical pieces, and the kernels then run 2-3% slower)
+        keep = []
         result["config"]["other_workloads"] = {
-            name: time_default_step(name, args.other_steps, 10) for name in ("c3", "c5", "c2", "c1")}
+            name: time_default_step(name, args.other_steps, 10, keep) for name in ("c3", "c5", "c2", "c1")}
     print(json.dumps(result), flush=True)
 
 
