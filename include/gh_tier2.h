@@ -50,10 +50,11 @@
  *     rows kT .. kT+T-1 form group k and address one slot; each row keeps its
  *     own ctx_len (and q, position, output row).  gh_decode_attention then
  *     fetches the slot's K/V rows from memory once per 128 of the T*G query
- *     heads a group has per kv head -- a wave carries 32 of them as the head
- *     columns of two matrix-core tiles fed from one stream of rows, up to four
- *     waves of a workgroup walk the same rows together, and each column is
- *     masked at its own token's length -- instead of once per row.  A
+ *     heads a group has per kv head -- a wave carries 16 or 32 of them as the
+ *     head columns of one or two matrix-core tiles fed from one stream of rows;
+ *     beyond 32 the four waves of a workgroup stream the rows once between them
+ *     (through LDS); each column is masked at its own token's length --
+ *     instead of once per row.  A
  *     row with ctx_len 0, a bad slot id, or a slot other than that of the
  *     group's first live row gets no rows (output zero), so short groups are
  *     padded with ctx_len = 0 rows and a decode entry is a group with one live
@@ -189,12 +190,12 @@ size_t gh_decode_workspace_bytes(const gh_problem* p);
  */
 typedef struct {
   int32_t balanced;           /* 0: fixed split, the other fields are 0          */
-  int32_t n_workers;          /* workers (waves, or sets of waves_per_worker)    */
+  int32_t n_workers;          /* workers (waves, or workgroups of four waves)    */
   int32_t min_share;          /* least tiles per worker                          */
   int32_t passes_per_strip;   /* 1 or 2                                          */
   int32_t strips_per_kv_head; /* pass sets per (group, kv head)                  */
   int32_t n_chunks;           /* = gh_decode_num_chunks                          */
-  int32_t waves_per_worker;   /* 1, 2 or 4: the waves of a worker walk the same
+  int32_t waves_per_worker;   /* 1 or 4: the waves of a worker walk the same
                                  tiles, each with its own passes_per_strip passes
                                  (a strip then stands for their product of passes) */
 } gh_split_plan;

@@ -2,7 +2,10 @@
 //
 // One wave owns one (sequence, kv head, head pass, chunk) and walks it in
 // tiles of 32 rows.  No LDS and no barrier: both operands are loaded from
-// global memory straight into the register layout the MFMA wants.
+// global memory straight into the register layout the MFMA wants.  (The one
+// exception -- head groups or token groups of more than 32 head columns, which
+// are bound by arithmetic and not by the stream -- is the cooperative form of
+// the balanced kernel: process_tile_lds below.)
 //
 // Lane numbering: hn = lane % 16, c = lane / 16.
 //
@@ -135,34 +138,66 @@ __device__ __forceinline__ void load_tile(TileRegs& t, const char* kt, const cha
   }
 }
 
+// A quarter of a tile: what one of the four waves of a cooperating workgroup fetches of it.  Wave w
+// takes the K registers of (T, ab) = (w >> 1, w & 1) -- eight whole 256-byte rows -- and the V
+// registers e = 2w, 2w + 1 -- eight whole rows too.
+struct PartRegs {
+  u32x4 k[2];        // [128-byte half of the row]
+  u32x4 v[2];        // [e - 2w]
+};
+template <bool NT>
+__device__ __forceinline__ void load_part(PartRegs& pr, const char* kt, const char* vt,
+                                          uint32_t row_bytes, int rows, const LaneGeom& lg, int w) {
+  const int top = rows - 1;
+  int r = lg.krow + 16 * (w >> 1) + 2 * (w & 1);
+  r = r < top ? r : top;
+  const uint32_t off = __umul24((uint32_t)r, row_bytes) + lg.kcol;
+#pragma unroll
+  for (int half = 0; half < 2; ++half) pr.k[half] = stream_load_at<NT>(kt, off + 128 * half);
+#pragma unroll
+  for (int j = 0; j < 2; ++j) {
+    const int e = 2 * w + j;
+    int rv = lg.vrow + 16 * (e >> 2) + 4 * (e & 3);
+    rv = rv < top ? rv : top;
+    pr.v[j] = stream_load_at<NT>(vt, __umul24((uint32_t)rv, row_bytes) + lg.vcol);
+  }
+}
+// The tile the four waves put together in LDS: the 32 K rows and the 32 V rows as they lie in the
+// cache, 256 bytes each, at a pitch of 272 bytes -- so that the 16 rows a 16-lane group reads at
+// the same byte column fall into 16 different groups of four banks.
+constexpr int kLdsPitch = 272;
+struct __attribute__((aligned(16))) TileLds {
+  char k[32 * kLdsPitch];
+  char v[32 * kLdsPitch];
+};
+__device__ __forceinline__ void put_part(TileLds& x, const PartRegs& pr, int w, const LaneGeom& lg) {
+  const int rk = lg.krow + 16 * (w >> 1) + 2 * (w & 1);
+#pragma unroll
+  for (int half = 0; half < 2; ++half)
+    *reinterpret_cast<u32x4*>(x.k + rk * kLdsPitch + lg.kcol + 128 * half) = pr.k[half];
+#pragma unroll
+  for (int j = 0; j < 2; ++j) {
+    const int e = 2 * w + j;
+    const int rv = lg.vrow + 16 * (e >> 2) + 4 * (e & 3);
+    *reinterpret_cast<u32x4*>(x.v + rv * kLdsPitch + lg.vcol) = pr.v[j];
+  }
+}
+
 // One 32-row tile for P passes of 16 head columns each (own Q operand, running state and
 // accumulators per pass; the K operands and the transposed V operands are built once).  `lim` is
 // the number of rows the lane's head column attends (rows at or beyond it are masked); columns of
 // one tile may have different limits, and a column may have no row at all in a tile.
-template <bool BF16, int P>
-__device__ __forceinline__ void process_tile(const TileRegs& t, const u32x4 (&qop)[P][4],
-                                             f32x4 (&acc)[P][8], float (&m)[P], float (&l)[P],
+// The online-softmax update of one tile for P passes: from the raw scores s (register e = 4T + i of
+// lane (hn, c) is head column hn against tile row 16T + 4i + c) to the probabilities as two 16-bit
+// operands (hi + lo), with the running exponent m and sum l brought up to date and the accumulators
+// rescaled when the exponent moved.  `lim` is the number of rows the lane's head column attends
+// (rows at or beyond it are masked); columns of one tile may have different limits, and a column
+// may have no row at all in a tile.
+template <bool BF16, int P, int NT>
+__device__ __forceinline__ void softmax_tile(const f32x4 (&s)[P][2], u32x4 (&p_hi)[P], u32x4 (&p_lo)[P],
+                                             f32x4 (&acc)[P][NT], float (&m)[P], float (&l)[P],
                                              float scale_log2e, int tile_row0, const int (&lim)[P],
                                              int c) {
-  // scores of head hn against this lane's 8 rows
-  f32x4 s[P][2];
-#pragma unroll
-  for (int T = 0; T < 2; ++T) {
-#pragma unroll
-    for (int i = 0; i < P; ++i) s[i][T] = f32x4{0.f, 0.f, 0.f, 0.f};
-#pragma unroll
-    for (int half = 0; half < 2; ++half) {
-      // operand of d step kk: lane (hn, c) holds d-chunk 4kk + c of row rho(T, hn)
-      const u32x4 k_even = upper_from_rotated(t.k[T][half][0], t.k[T][half][1]);   // kk = 2*half
-      const u32x4 k_odd = lower_from_rotated(t.k[T][half][1], t.k[T][half][0]);    // kk = 2*half + 1
-#pragma unroll
-      for (int i = 0; i < P; ++i) {
-        s[i][T] = mfma<BF16>(k_even, qop[i][2 * half], s[i][T]);
-        s[i][T] = mfma<BF16>(k_odd, qop[i][2 * half + 1], s[i][T]);
-      }
-    }
-  }
-  u32x4 p_hi[P], p_lo[P];
 #pragma unroll
   for (int i = 0; i < P; ++i) {
     float tv[8];
@@ -216,9 +251,38 @@ __device__ __forceinline__ void process_tile(const TileRegs& t, const u32x4 (&qo
     }
     if (__any(moved)) {
 #pragma unroll
-      for (int tcol = 0; tcol < 8; ++tcol) acc[i][tcol] *= alpha;
+      for (int tcol = 0; tcol < NT; ++tcol) acc[i][tcol] *= alpha;
     }
   }
+}
+
+// One 32-row tile for P passes of 16 head columns each (own Q operand, running state and
+// accumulators per pass; the K operands and the transposed V operands are built once).
+template <bool BF16, int P>
+__device__ __forceinline__ void process_tile(const TileRegs& t, const u32x4 (&qop)[P][4],
+                                             f32x4 (&acc)[P][8], float (&m)[P], float (&l)[P],
+                                             float scale_log2e, int tile_row0, const int (&lim)[P],
+                                             int c) {
+  // scores of head hn against this lane's 8 rows
+  f32x4 s[P][2];
+#pragma unroll
+  for (int T = 0; T < 2; ++T) {
+#pragma unroll
+    for (int i = 0; i < P; ++i) s[i][T] = f32x4{0.f, 0.f, 0.f, 0.f};
+#pragma unroll
+    for (int half = 0; half < 2; ++half) {
+      // operand of d step kk: lane (hn, c) holds d-chunk 4kk + c of row rho(T, hn)
+      const u32x4 k_even = upper_from_rotated(t.k[T][half][0], t.k[T][half][1]);   // kk = 2*half
+      const u32x4 k_odd = lower_from_rotated(t.k[T][half][1], t.k[T][half][0]);    // kk = 2*half + 1
+#pragma unroll
+      for (int i = 0; i < P; ++i) {
+        s[i][T] = mfma<BF16>(k_even, qop[i][2 * half], s[i][T]);
+        s[i][T] = mfma<BF16>(k_odd, qop[i][2 * half + 1], s[i][T]);
+      }
+    }
+  }
+  u32x4 p_hi[P], p_lo[P];
+  softmax_tile<BF16, P, 8>(s, p_hi, p_lo, acc, m, l, scale_log2e, tile_row0, lim, c);
   // O^T += V^T P^T, one 16-column tile at a time
 #pragma unroll
   for (int tcol = 0; tcol < 8; ++tcol) {
@@ -233,6 +297,51 @@ __device__ __forceinline__ void process_tile(const TileRegs& t, const u32x4 (&qo
     for (int i = 0; i < P; ++i) {
       acc[i][tcol] = mfma<BF16>(vt, p_hi[i], acc[i][tcol]);
       acc[i][tcol] = mfma<BF16>(vt, p_lo[i], acc[i][tcol]);
+    }
+  }
+}
+
+// The same tile taken from LDS (TileLds), operands read in the layout the matrix instruction wants:
+//   K: lane (hn, c) reads the 16 bytes of d-chunk 4kk + c of row rho(T, hn) = 16T + 4(hn & 3) + (hn >> 2);
+//   V^T: a transposing read -- lane j of 16-lane group c hands in the address of four consecutive
+//        columns 16t + 4(j & 3) .. of row 16T + 4(j >> 2) + c, and receives column 16t + j of the
+//        group's four rows 16T + 4i + c, i = 0..3: contraction slots e = 4T + i of column 16t + j.
+// So here result register r of lane (hn, c) in column tile t is column 16t + 4c + r of head hn
+// (acc_natural), not the layout of process_tile: the stores that follow differ (store_*_natural).
+typedef short v4s __attribute__((ext_vector_type(4)));
+template <bool BF16, int P>
+__device__ __forceinline__ void process_tile_lds(const TileLds& x, const u32x4 (&qop)[P][4],
+                                                 f32x4 (&acc)[P][8], float (&m)[P], float (&l)[P],
+                                                 float scale_log2e, int tile_row0,
+                                                 const int (&lim)[P], int hn, int c) {
+  f32x4 s[P][2];
+#pragma unroll
+  for (int T = 0; T < 2; ++T) {
+#pragma unroll
+    for (int i = 0; i < P; ++i) s[i][T] = f32x4{0.f, 0.f, 0.f, 0.f};
+    const char* row = x.k + (16 * T + 4 * (hn & 3) + (hn >> 2)) * kLdsPitch + 16 * c;
+#pragma unroll
+    for (int kk = 0; kk < 4; ++kk) {
+      const u32x4 kop = *reinterpret_cast<const u32x4*>(row + 64 * kk);
+#pragma unroll
+      for (int i = 0; i < P; ++i) s[i][T] = mfma<BF16>(kop, qop[i][kk], s[i][T]);
+    }
+  }
+  u32x4 p_hi[P], p_lo[P];
+  softmax_tile<BF16, P, 8>(s, p_hi, p_lo, acc, m, l, scale_log2e, tile_row0, lim, c);
+  const char* vrow = x.v + (4 * (hn >> 2) + c) * kLdsPitch + 8 * (hn & 3);
+#pragma unroll
+  for (int t = 0; t < 8; ++t) {
+    typedef v4s __attribute__((address_space(3))) * lds_v4s;
+    const v4s lo = __builtin_amdgcn_ds_read_tr16_b64_v4i16((lds_v4s)(vrow + 32 * t));
+    const v4s hi = __builtin_amdgcn_ds_read_tr16_b64_v4i16((lds_v4s)(vrow + 16 * kLdsPitch + 32 * t));
+    typedef uint32_t u32x2 __attribute__((ext_vector_type(2)));
+    const u32x2 a = __builtin_bit_cast(u32x2, lo), b = __builtin_bit_cast(u32x2, hi);
+    const u32x4 vt = {a[0], a[1], b[0], b[1]};
+#pragma unroll
+    for (int i = 0; i < P; ++i) {
+      acc[i][t] = mfma<BF16>(vt, p_hi[i], acc[i][t]);
+      acc[i][t] = mfma<BF16>(vt, p_lo[i], acc[i][t]);
     }
   }
 }
@@ -414,6 +523,55 @@ __device__ __forceinline__ void store_final(const AttnArgs& a, int b, int g, int
         __builtin_amdgcn_raw_buffer_store_b64(lo, dst, at * 2, 0, kWriteThrough);
         __builtin_amdgcn_raw_buffer_store_b64(hi, dst, (at + 32) * 2, 0, kWriteThrough);
       }
+    }
+  }
+}
+
+// The same two stores for accumulators in the layout of process_tile_lds: register r of column tile
+// t is column 16t + 4c + r, so a lane writes eight 16-byte pieces per head column and the four lanes
+// of a head cover 64 bytes per instruction.  (These are the stores of launches that are bound by
+// arithmetic, not by the memory stream: half lines are good enough.)
+__device__ __forceinline__ void store_record_natural(const AttnArgs& a, int b, int g, int pass, int nh,
+                                                     int slot, const f32x4 (&acc)[8], float m, float l,
+                                                     int hn, int c) {
+  l = rows_sum(l);
+  const int64_t pitch = (int64_t)a.n_chunks * kHeadDim;
+  const int64_t first = column_index(a, b, g, pass, 0);
+  const int64_t last = column_index(a, b, g, pass, nh - 1);
+  float* base = a.ws_o + (first * a.n_chunks + slot) * kHeadDim;
+  const __amdgpu_buffer_rsrc_t rec = __builtin_amdgcn_make_buffer_rsrc(
+      base, 0, (int)(((last - first) * pitch + kHeadDim) * 4), kRawBufferFlags);
+  if (hn < nh) {
+    const int64_t mine = column_index(a, b, g, pass, hn);
+    const int at = (int)(((mine - first) * pitch + 4 * c) * 4);
+#pragma unroll
+    for (int t = 0; t < 8; ++t)
+      __builtin_amdgcn_raw_buffer_store_b128(__builtin_bit_cast(u32x4, acc[t]), rec, at + 64 * t, 0,
+                                             kWriteThrough);
+    if (c == 0) {
+      a.ws_m[mine * a.n_chunks + slot] = m;
+      a.ws_l[mine * a.n_chunks + slot] = l;
+    }
+  }
+}
+template <bool BF16>
+__device__ __forceinline__ void store_final_natural(const AttnArgs& a, int b, int g, int pass, int nh,
+                                                    const f32x4 (&acc)[8], float l, int hn, int c) {
+  typedef uint32_t u32x2 __attribute__((ext_vector_type(2)));
+  l = rows_sum(l);
+  if (hn >= nh) return;
+  const int64_t at = column_index(a, b, g, pass, hn) * kHeadDim + 4 * c;
+#pragma unroll
+  for (int t = 0; t < 8; ++t) {
+    f32x4 x;
+#pragma unroll
+    for (int e = 0; e < 4; ++e)            // (+ 0: the merge's 1 * o + 0 turns a -0 into +0)
+      x[e] = l > 0.f ? (acc[t][e] + 0.f) / l : 0.f;
+    if (a.out_kind == 1) {
+      *reinterpret_cast<f32x4*>(static_cast<float*>(a.out) + at + 16 * t) = x;
+    } else {
+      const u32x2 w = {pack2<BF16>(x[0], x[1]), pack2<BF16>(x[2], x[3])};
+      *reinterpret_cast<u32x2*>(static_cast<uint16_t*>(a.out) + at + 16 * t) = w;
     }
   }
 }
@@ -645,17 +803,23 @@ struct TileCursor {
   uint32_t tiles;   // tiles per strip of this sequence (>= 1)
   int n;            // rows attended of this sequence
   int slot;         // cache slot (0 when n == 0)
+  // kept for the cursors that address tiles (not for the one that runs ahead for Q rows):
+  int g;            // kv head of the strip
+  int64_t strip;    // element offset of the strip's row 0 in the caches
+  int64_t off;      // element offset of the tile's first row inside the strip
 };
 
 //
 // P = passes of 16 head columns a wave carries through a strip at once (own Q operand, running
 // state and accumulators per pass, one stream of tiles for all): 1 for decode, 2 for token groups
 // with more than 16 head columns, at one wave per SIMD instead of two.
-// SHARED: the waves of a workgroup walk the same tiles in sets of a.share (> 1), see below.
+// COOP: the four waves of a workgroup are one worker: they walk the same tiles, each with its own P
+//       passes, fetch a quarter of every tile each and hand the quarters to one another through LDS.
 // FUSED: the whole step in one launch (see AttnArgs): append, attention and merge.
-template <bool BF16, bool GROUPED, int P, bool SHARED, bool FUSED>
-__global__ __launch_bounds__(256, P == 1 ? 2 : 1) void attn_mfma_balanced_kernel(const AttnArgs a) {
+template <bool BF16, bool GROUPED, int P, bool COOP, bool FUSED>
+__global__ __launch_bounds__(256, COOP || P == 1 ? 2 : 1) void attn_mfma_balanced_kernel(const AttnArgs a) {
   static_assert(!(FUSED && GROUPED), "the one-launch step is for batches of one token per slot");
+  static_assert(!(FUSED && COOP), "the one-launch step runs a wave per worker");
   constexpr int kThreads = 256;
   extern __shared__ uint32_t lds[];
   __shared__ uint32_t part[kThreads];
@@ -678,6 +842,10 @@ __global__ __launch_bounds__(256, P == 1 ? 2 : 1) void attn_mfma_balanced_kernel
         if ((bad_slot || bad_pos) && a.dev_status && blockIdx.x == 0)
           atomicOr(a.dev_status, (bad_slot ? 1 : 0) | (bad_pos ? 2 : 0));
         nt = bad_pos ? 0 : nt + 1;
+      } else if (a.ctx_bias) {
+        // positions again, but the rows are appended already (the step as three kernels): a
+        // position out of range was skipped by the append and attends nothing
+        nt = nt < 0 || nt >= a.row_limit ? 0 : nt + 1;
       }
       nt = nt < a.row_limit ? nt : a.row_limit;
       if (st < 0 || st >= a.n_slots || nt <= 0) continue;
@@ -715,15 +883,13 @@ __global__ __launch_bounds__(256, P == 1 ? 2 : 1) void attn_mfma_balanced_kernel
   const uint32_t total = uni(cum[B]);
   const int lane = tid & 63;
   const int hn = lane & 15, c = lane >> 4;
-  // Worker = `share` consecutive waves of a workgroup (1, 2 or 4) that walk the same tiles, each
-  // with its own passes; gw numbers the workers.  The waves of a worker run the same instruction
-  // stream on the same addresses at nearly the same time, so the tile is fetched from memory once
-  // and the other waves' loads are served by the cache.
+  // Worker: one wave, or (COOP) the four waves of the workgroup, which walk the same tiles, each
+  // with its own passes; gw numbers the workers.
   const uint32_t wave = uni(tid >> 6);
-  const uint32_t n_share = SHARED ? (uint32_t)a.share : 1u;
-  const uint32_t gw = (blockIdx.x * 4 + wave) / n_share;
-  const int wsub = (int)(wave % n_share) * P;                  // first pass of this wave in a strip's set
-  uint32_t share = (total + a.n_workers - 1) / a.n_workers;    // tiles per wave
+  constexpr uint32_t n_share = COOP ? 4u : 1u;
+  const uint32_t gw = COOP ? blockIdx.x : blockIdx.x * 4 + wave;
+  const int wsub = COOP ? (int)wave * P : 0;                   // first pass of this wave in a strip's set
+  uint32_t share = (total + a.n_workers - 1) / a.n_workers;    // tiles per worker
   share = share > (uint32_t)a.min_share ? share : (uint32_t)a.min_share;
   const uint32_t t0 = gw * share;
   const uint32_t t_end = t0 + share < total ? t0 + share : total;
@@ -735,6 +901,15 @@ __global__ __launch_bounds__(256, P == 1 ? 2 : 1) void attn_mfma_balanced_kernel
     cu.n = (int)uni((uint32_t)rows[cu.b]);
     cu.slot = (int)uni((uint32_t)slots[cu.b]);
   };
+  // The address of a tile is kept up to date step by step (a few scalar additions per tile; worked
+  // out from scratch it is a division and five 64-bit products).
+  const int64_t tile_step = 32 * a.row_stride;
+  const int64_t block_jump = a.block_stride - ((int64_t)a.block_mask + 1) * a.row_stride;
+  auto enter_strip = [&](TileCursor& cu) {                     // cu.lt is 0
+    cu.g = (int)(cu.sib / (uint32_t)a.n_pass);
+    cu.strip = (int64_t)cu.slot * a.slot_stride + (int64_t)cu.g * a.head_stride;
+    cu.off = 0;
+  };
   auto advance = [&](TileCursor& cu) {                         // caller keeps cu.t + 1 < total
     ++cu.t;
     if (++cu.lt == cu.tiles) {
@@ -744,6 +919,11 @@ __global__ __launch_bounds__(256, P == 1 ? 2 : 1) void attn_mfma_balanced_kernel
         ++cu.b;
         enter_sequence(cu);
       }
+      enter_strip(cu);
+    } else {
+      cu.off += tile_step;
+      // (a blocked layout: the first tile of the next block; a plain one has a single block)
+      if (((cu.lt << 5) & (uint32_t)a.block_mask) == 0) cu.off += block_jump;
     }
   };
   // Strip `sib` of a group: kv head g, passes pass0 .. pass0 + P - 1 of which nh[i] columns are
@@ -779,18 +959,18 @@ __global__ __launch_bounds__(256, P == 1 ? 2 : 1) void attn_mfma_balanced_kernel
   };
   const LaneGeom lg = lane_geom(hn, c);
   const uint32_t row_bytes = (uint32_t)a.row_stride * 2u;
-  auto issue = [&](TileRegs& regs, const TileCursor& cu) {
-    const int g = (int)(cu.sib / (uint32_t)a.n_pass);
+  // Where the tile under a cursor is read from, and how many of its 32 rows exist.
+  auto tile_source = [&](const TileCursor& cu, const char*& kt, const char*& vt, int& rows) {
+    const int g = cu.g;
     const int row0 = (int)cu.lt * 32;
     // A strip without rows reads the first 256 bytes of q instead: the loads stay unconditional,
     // and no cache address is touched that the caller did not declare attended (a paged cache
     // may have nothing mapped there).
-    const char* kt = reinterpret_cast<const char*>(a.q);
-    const char* vt = kt;
-    int rows = 1;
+    kt = reinterpret_cast<const char*>(a.q);
+    vt = kt;
+    rows = 1;
     if (cu.n > 0) {
-      const int64_t at = (int64_t)cu.slot * a.slot_stride + (int64_t)g * a.head_stride +
-                         row_offset(row0, a.row_stride, a.block_stride, a.block_shift, a.block_mask);
+      const int64_t at = cu.strip + cu.off;
       kt = reinterpret_cast<const char*>(a.k_cache + at);
       vt = reinterpret_cast<const char*>(a.v_cache + at);
       rows = cu.n - row0;
@@ -804,9 +984,19 @@ __global__ __launch_bounds__(256, P == 1 ? 2 : 1) void attn_mfma_balanced_kernel
         }
       }
     }
-    // (a wave of its own reads every row once: keep the stream out of the caches' way; when several
-    // waves ask for the same rows, let the cache keep them)
-    load_tile<!SHARED>(regs, kt, vt, row_bytes, rows, lg);
+  };
+  // (every row is read once, by one wave: keep the stream out of the caches' way)
+  auto issue = [&](TileRegs& regs, const TileCursor& cu) {
+    const char *kt, *vt;
+    int rows;
+    tile_source(cu, kt, vt, rows);
+    load_tile<true>(regs, kt, vt, row_bytes, rows, lg);
+  };
+  auto issue_part = [&](PartRegs& pr, const TileCursor& cu) {
+    const char *kt, *vt;
+    int rows;
+    tile_source(cu, kt, vt, rows);
+    load_part<true>(pr, kt, vt, row_bytes, rows, lg, (int)wave);
   };
 
   // cursor of the tile being computed; start: largest b with cum[b] <= t0
@@ -826,6 +1016,8 @@ __global__ __launch_bounds__(256, P == 1 ? 2 : 1) void attn_mfma_balanced_kernel
     cp.sib = rem / cp.tiles;
     cp.lt = rem - cp.sib * cp.tiles;
   }
+  enter_strip(cp);
+  cp.off = row_offset((int)cp.lt * 32, a.row_stride, a.block_stride, a.block_shift, a.block_mask);
   TileCursor ld = cp;                                          // cursor of the next tile to load
   // cursor of the strip whose Q operand is fetched next (first tile of a strip, or past the end)
   TileCursor qs = cp;
@@ -902,7 +1094,8 @@ __global__ __launch_bounds__(256, P == 1 ? 2 : 1) void attn_mfma_balanced_kernel
   int n_part = 0;
 
   // One tile of arithmetic; closes the record when the tile ends this wave's piece of the strip.
-  auto compute = [&](const TileRegs& regs) {
+  // (the tile is in registers, or -- COOP -- in LDS)
+  auto compute = [&](const TileRegs* regs, const TileLds* shared) {
     // (a pass without columns runs on a zero operand; its results are never stored)
     const bool strip_end = cp.lt + 1 == cp.tiles;
     if (cp.n > 0) {
@@ -913,10 +1106,12 @@ __global__ __launch_bounds__(256, P == 1 ? 2 : 1) void attn_mfma_balanced_kernel
         int upto[P];
 #pragma unroll
         for (int i = 0; i < P; ++i) upto[i] = strip_end ? lim[i] : lim[i] - 1;
-        process_tile<BF16, P>(regs, qop, acc, m, l, a.scale_log2e,
+        process_tile<BF16, P>(*regs, qop, acc, m, l, a.scale_log2e,
                               strip_end ? cp.n - 1 : (int)cp.lt * 32, upto, c);
+      } else if constexpr (COOP) {
+        process_tile_lds<BF16, P>(*shared, qop, acc, m, l, a.scale_log2e, (int)cp.lt * 32, lim, hn, c);
       } else {
-        process_tile<BF16, P>(regs, qop, acc, m, l, a.scale_log2e, (int)cp.lt * 32, lim, c);
+        process_tile<BF16, P>(*regs, qop, acc, m, l, a.scale_log2e, (int)cp.lt * 32, lim, c);
       }
     }
     if constexpr (FUSED) {
@@ -924,7 +1119,7 @@ __global__ __launch_bounds__(256, P == 1 ? 2 : 1) void attn_mfma_balanced_kernel
       if (strip_end && cp.n > 0 && cp.sib % (uint32_t)a.n_pass == 0 && wsub == 0) {
         const int64_t at = (int64_t)cp.slot * a.slot_stride + (int64_t)g * a.head_stride +
                            row_offset(cp.n - 1, a.row_stride, a.block_stride, a.block_shift, a.block_mask);
-        store_new_row(regs, reinterpret_cast<char*>(const_cast<uint16_t*>(a.k_cache) + at),
+        store_new_row(*regs, reinterpret_cast<char*>(const_cast<uint16_t*>(a.k_cache) + at),
                       reinterpret_cast<char*>(const_cast<uint16_t*>(a.v_cache) + at), 0, lg);
       }
     }
@@ -938,10 +1133,16 @@ __global__ __launch_bounds__(256, P == 1 ? 2 : 1) void attn_mfma_balanced_kernel
 #pragma unroll
         for (int i = 0; i < P; ++i) {
           if (nh[i] == 0) continue;
-          if (whole)
+          if constexpr (COOP) {
+            if (whole)
+              store_final_natural<BF16>(a, cp.b, g, pass0 + i, nh[i], acc[i], l[i], hn, c);
+            else
+              store_record_natural(a, cp.b, g, pass0 + i, nh[i], rec, acc[i], m[i], l[i], hn, c);
+          } else if (whole) {
             store_final<BF16>(a, cp.b, g, pass0 + i, nh[i], acc[i], l[i], hn, c);
-          else
+          } else {
             store_record(a, cp.b, g, pass0 + i, nh[i], rec, acc[i], m[i], l[i], hn, c);
+          }
         }
         if (FUSED && !whole) {
           // (slot 1 when slot 0 is taken: registers, not an indexed array)
@@ -1007,25 +1208,63 @@ __global__ __launch_bounds__(256, P == 1 ? 2 : 1) void attn_mfma_balanced_kernel
     }
   };
 
-  // Two register tiles: one is in flight while the other is computed.  Loads are issued
-  // unconditionally (past the end of the share the last position is loaded again, from cache) so
-  // that every wait count is exact.  (A third tile in flight was measured for the two-pass
-  // instantiation, which has the registers for it: no change -- it is not waiting for memory.)
-  auto load_next = [&](TileRegs& regs) {
-    if (ld.t + 1 < t_end) advance(ld);
-    issue(regs, ld);
-  };
-  TileRegs ta, tb;
-  issue(ta, ld);
-  while (true) {
-    load_next(tb);
-    compute(ta);
-    if (cp.t + 1 >= t_end) break;
-    advance(cp);
-    load_next(ta);
-    compute(tb);
-    if (cp.t + 1 >= t_end) break;
-    advance(cp);
+  if constexpr (COOP) {
+    // Each wave keeps its quarters of the next two tiles in flight (four were measured: no faster,
+    // and two leave the registers for two workgroups per compute unit).  Per tile: put the quarter
+    // that has arrived into the LDS tile, ask for the quarter two tiles on, meet the other waves,
+    // compute from LDS.  Two LDS tiles and one barrier per tile: the tile written before
+    // barrier i is read after it, and is written again only after barrier i + 1, which no wave
+    // passes before all have finished reading.  The four waves run the same tiles to the same end,
+    // so every wave reaches every barrier.
+    __shared__ TileLds exchange[2];
+    auto next_part = [&](PartRegs& pr) {
+      if (ld.t + 1 < t_end) advance(ld);
+      issue_part(pr, ld);
+    };
+    PartRegs p0, p1;
+    issue_part(p0, ld);
+    next_part(p1);
+    int buf = 0;
+    // (Steps come two to a loop iteration, one per register quarter, and the loop has a single
+    // exit: a step past the worker's last tile still puts, loads -- the last position again -- and
+    // meets the others, and skips the arithmetic.  With an exit after every step the paths that
+    // leave would join the loop's back edge, and the wait before the first put of an iteration
+    // would be for everything in flight instead of for that quarter.)
+    bool live = true;
+    auto step = [&](PartRegs& pr) {
+      put_part(exchange[buf], pr, (int)wave, lg);
+      next_part(pr);
+      __syncthreads();
+      if (live) {
+        compute(nullptr, &exchange[buf]);
+        if (cp.t + 1 >= t_end) live = false; else advance(cp);
+      }
+      buf ^= 1;
+    };
+    do {
+      step(p0);
+      step(p1);
+    } while (live);
+  } else {
+    // Two register tiles: one is in flight while the other is computed.  Loads are issued
+    // unconditionally (past the end of the share the last position is loaded again, from cache) so
+    // that every wait count is exact.
+    auto load_next = [&](TileRegs& regs) {
+      if (ld.t + 1 < t_end) advance(ld);
+      issue(regs, ld);
+    };
+    TileRegs ta, tb;
+    issue(ta, ld);
+    while (true) {
+      load_next(tb);
+      compute(&ta, nullptr);
+      if (cp.t + 1 >= t_end) break;
+      advance(cp);
+      load_next(ta);
+      compute(&tb, nullptr);
+      if (cp.t + 1 >= t_end) break;
+      advance(cp);
+    }
   }
 
   if constexpr (FUSED) {

@@ -121,8 +121,9 @@ struct Plan {
   int n_workers, min_share; // balanced split only
   int passes_per_strip;     // balanced split: passes a wave carries through a strip at once;
                             // n_pass then counts strips per (group, kv head)
-  int share;                // balanced split: waves per worker; the waves of a worker walk the same
-                            // tiles, each with its own passes_per_strip passes
+  int share;                // balanced split: waves per worker (1, or 4: a whole workgroup); the
+                            // waves of a worker walk the same tiles, each with its own
+                            // passes_per_strip passes
 };
 
 constexpr int kBalancedWavesPerCU = 8;      // resident waves of the MFMA kernel per compute unit
@@ -137,14 +138,18 @@ inline Plan make_plan(const gh_problem* p) {
   pl.passes_per_strip = 1;
   pl.share = 1;
   const int groups = p->batch / tokens_per_group(p);
-  // More than 16 head columns per kv head (a token group, or a head group above 16): two passes
-  // share one stream of tiles, at one wave per SIMD (the second pass's operands and accumulators
-  // take the other wave's registers).
-  const int pps = pl.n_pass > 1 ? 2 : 1;
-  // More than 32: up to four waves of a workgroup share one stream of tiles, so that K/V rows are
-  // read from memory once per 128 head columns.
+  // Head columns per kv head (a head group, or a token group's heads) in passes of 16:
+  //   up to 16: a wave carries one pass, two waves per SIMD;
+  //   up to 32: a wave carries two passes through one stream of tiles, at one wave per SIMD (the
+  //             second pass's operands and accumulators take the other wave's registers);
+  //   more:     the four waves of a workgroup form one worker that streams the tiles once -- each
+  //             wave fetches a quarter, they put the tile together in LDS and read their operands
+  //             from there -- with one pass per wave (up to 64 columns) or two (up to 128 columns
+  //             per strip), two workgroups per compute unit.  K/V rows are read from memory once
+  //             per 128 head columns.
+  const int pps = pl.n_pass == 2 || pl.n_pass > 4 ? 2 : 1;
+  const int share = pl.n_pass > 2 ? 4 : 1;
   const int sets = (pl.n_pass + pps - 1) / pps;
-  const int share = sets >= 3 ? 4 : sets;
   const int n_strip = (sets + share - 1) / share;
   const int64_t strips = (int64_t)(groups > 0 ? groups : 1) * p->n_kv_heads * n_strip;
   // (+ 1: the one-launch step walks the appended row as a tile of its own behind the cached rows)
@@ -157,7 +162,10 @@ inline Plan make_plan(const gh_problem* p) {
     pl.passes_per_strip = pps;
     pl.n_pass = n_strip;
     pl.share = share;
-    pl.n_workers = kComputeUnits * (pps == 1 ? kBalancedWavesPerCU : kBalancedWavesPerCU / 2) / share;
+    // workers: a wave each, as many as are resident (eight per compute unit with one pass, four
+    // with two); or a workgroup each, two per compute unit
+    pl.n_workers = share == 4 ? kComputeUnits * 2
+                              : kComputeUnits * (pps == 1 ? kBalancedWavesPerCU : kBalancedWavesPerCU / 2);
     int64_t c = (4 * (int64_t)pl.n_workers + strips - 1) / strips + 1;
     if (c < 2) c = 2;
     if (c > kBalancedMaxRecords) c = kBalancedMaxRecords;

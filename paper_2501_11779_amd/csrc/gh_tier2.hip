@@ -20,28 +20,32 @@ namespace {
 
 using namespace gh_plan;
 
-// Instantiations of the balanced kernel: dtype x (token groups) x (one pass per wave | two passes,
-// alone or with the workgroup's waves sharing a stream).
+// Instantiations of the balanced kernel: dtype x (token groups) x (one | two passes per wave) x
+// (a wave per worker | the workgroup's four waves as one worker).
 template <bool BF16, bool GROUPED, bool FUSED>
-void launch_balanced_as(const gh::AttnArgs& a, int passes, bool shared, size_t lds, hipStream_t s) {
-  const dim3 grid(a.n_workers * a.share / 4), block(256);
-  if (passes == 1)
+void launch_balanced_as(const gh::AttnArgs& a, int passes, bool coop, size_t lds, hipStream_t s) {
+  const dim3 grid(coop ? a.n_workers : a.n_workers / 4), block(256);
+  if (passes == 1 && !coop)
     hipLaunchKernelGGL((gh::attn_mfma_balanced_kernel<BF16, GROUPED, 1, false, FUSED>), grid, block, lds, s, a);
-  else if (!shared)
+  else if (passes == 2 && !coop)
     hipLaunchKernelGGL((gh::attn_mfma_balanced_kernel<BF16, GROUPED, 2, false, FUSED>), grid, block, lds, s, a);
-  else
-    hipLaunchKernelGGL((gh::attn_mfma_balanced_kernel<BF16, GROUPED, 2, true, FUSED>), grid, block, lds, s, a);
+  else if constexpr (!FUSED) {         // (the caller keeps the one-launch step off cooperative plans)
+    if (passes == 1)
+      hipLaunchKernelGGL((gh::attn_mfma_balanced_kernel<BF16, GROUPED, 1, true, false>), grid, block, lds, s, a);
+    else
+      hipLaunchKernelGGL((gh::attn_mfma_balanced_kernel<BF16, GROUPED, 2, true, false>), grid, block, lds, s, a);
+  }
 }
 // fused: the one-launch step (never with token groups)
 void launch_balanced(const gh::AttnArgs& a, bool bf16, bool grouped, bool fused, int passes,
-                     bool shared, size_t lds, hipStream_t s) {
+                     bool coop, size_t lds, hipStream_t s) {
   if (fused) {
-    if (bf16) launch_balanced_as<true, false, true>(a, passes, shared, lds, s);
-    else launch_balanced_as<false, false, true>(a, passes, shared, lds, s);
-  } else if (bf16 && grouped) launch_balanced_as<true, true, false>(a, passes, shared, lds, s);
-  else if (bf16) launch_balanced_as<true, false, false>(a, passes, shared, lds, s);
-  else if (grouped) launch_balanced_as<false, true, false>(a, passes, shared, lds, s);
-  else launch_balanced_as<false, false, false>(a, passes, shared, lds, s);
+    if (bf16) launch_balanced_as<true, false, true>(a, passes, coop, lds, s);
+    else launch_balanced_as<false, false, true>(a, passes, coop, lds, s);
+  } else if (bf16 && grouped) launch_balanced_as<true, true, false>(a, passes, coop, lds, s);
+  else if (bf16) launch_balanced_as<true, false, false>(a, passes, coop, lds, s);
+  else if (grouped) launch_balanced_as<false, true, false>(a, passes, coop, lds, s);
+  else launch_balanced_as<false, false, false>(a, passes, coop, lds, s);
 }
 
 template <bool BF16>
@@ -224,8 +228,10 @@ int32_t launch_attention(const gh_problem* p, const void* q, const void* k_cache
   const bool bf16 = p->dtype == GH_BF16;
   if (pl.balanced) {
     const size_t lds = (size_t)(3 * a.batch + 1) * sizeof(uint32_t);
-    launch_balanced(a, bf16, a.tokens > 1, step.k_new != nullptr, pl.passes_per_strip, pl.share > 1,
-                    lds, s);
+    // (the one-launch step runs a wave per worker; with cooperative workers gh_decode_step takes
+    // the three-kernel route, and this launch only reads positions instead of lengths)
+    launch_balanced(a, bf16, a.tokens > 1, step.k_new != nullptr && pl.share == 1,
+                    pl.passes_per_strip, pl.share > 1, lds, s);
   } else if (pl.kernel == GH_KERNEL_MFMA) {
     const dim3 grid(a.n_items), block(64);
     if (bf16)
@@ -428,11 +434,12 @@ int32_t gh_decode_step(const gh_problem* p, const void* q, const void* k_new, co
   if (p->kernel == GH_KERNEL_STRIPS && p->chunk_rows == 0)
     return launch_strips(p, q, k_new, v_new, k_cache, v_cache, slot_id, pos, out,
                          out_kind == GH_OUT_F32 ? 1 : 2, dev_status, 4, hip_stream);
-  if (pl.balanced)
+  if (pl.balanced && pl.share == 1)
     return launch_attention(p, q, k_cache, v_cache, slot_id, pos, workspace, workspace_bytes, out,
                             out_kind == GH_OUT_F32 ? 1 : 2, hip_stream, step);
-  // Fixed split, vector kernel or a batch beyond the balanced split: the same result from the
-  // three kernels, with the same rule for positions out of range.
+  // Fixed split, vector kernel, a batch beyond the balanced split or head groups so large that
+  // workgroups work as one (more than 32 heads per kv head): the same result from the three
+  // kernels, with the same rule for positions out of range.
   gh_problem bounded = *p;
   bounded.slot_capacity = p->max_ctx_len < p->slot_capacity ? p->max_ctx_len : p->slot_capacity;
   const int32_t ast = gh_kv_append(&bounded, k_cache, v_cache, k_new, v_new, slot_id, pos, dev_status,

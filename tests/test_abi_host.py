@@ -265,13 +265,13 @@ def test_split_plan_reports_the_fixed_split_and_checks_its_arguments():
     # 16 tokens of 8 heads per kv head: 128 head columns = four waves of two passes on one stream
     four = G.gh_decode_split_plan(good(batch=64, tokens_per_group=16, n_q_heads=64, n_kv_heads=8))
     assert (four.passes_per_strip, four.waves_per_worker, four.strips_per_kv_head, four.n_workers) \
-        == (2, 4, 1, 256)
-    # 64 tokens: 512 columns = four such strips; 3 passes: two waves, the second half empty
+        == (2, 4, 1, 512)
+    # 64 tokens: 512 columns = four such strips; 3 passes: four waves of one pass, the last without columns
     assert G.gh_decode_split_plan(good(batch=64, tokens_per_group=64, n_q_heads=64, n_kv_heads=8)
                                   ).strips_per_kv_head == 4
     three = G.gh_decode_split_plan(good(n_q_heads=40, n_kv_heads=1, strides=(4097 * 128, 4097 * 128, 128)))
     assert (three.passes_per_strip, three.waves_per_worker, three.strips_per_kv_head, three.n_workers) \
-        == (2, 2, 1, 512)
+        == (1, 4, 1, 512)
 
 
 def test_public_headers_are_plain_c(tmp_path):
