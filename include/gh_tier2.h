@@ -297,8 +297,9 @@ int32_t gh_decode_reduce_native(const gh_problem* p, const void* workspace,
  *     them zero again.  Two steps that overlap in time need two workspaces.
  *   - out / out_kind as for gh_decode_attention_out; every row of `out` is
  *     written.  Deterministic for given inputs (fixed summation order).
- *   - With a fixed split (chunk_rows > 0), GH_KERNEL_VALU or a batch beyond the
- *     balanced split the call issues the three kernels instead, same result.
+ *   - With a fixed split (chunk_rows > 0), GH_KERNEL_VALU, a batch beyond the
+ *     balanced split or more than 32 query heads per kv head the call issues
+ *     the three kernels instead, same result.
  *   - kernel = GH_KERNEL_STRIPS (with chunk_rows = 0): one workgroup per strip,
  *     see gh_kernel; the workspace is then not touched.
  */

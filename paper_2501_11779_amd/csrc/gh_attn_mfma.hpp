@@ -138,31 +138,36 @@ __device__ __forceinline__ void load_tile(TileRegs& t, const char* kt, const cha
   }
 }
 
-// A quarter of a tile: what one of the four waves of a cooperating workgroup fetches of it.  Wave w
-// takes the K registers of (T, ab) = (w >> 1, w & 1) -- eight whole 256-byte rows -- and the V
-// registers e = 2w, 2w + 1 -- eight whole rows too.
+// A share of a tile: what one of the W (2 or 4) waves of a cooperating workgroup fetches of it.  The
+// tile's K registers come in four pairs (T, ab) of eight whole 256-byte rows, its V registers e in
+// eight groups of four whole rows; wave w takes pairs w * 4/W .. and registers w * 8/W .. .
+template <int W>
 struct PartRegs {
-  u32x4 k[2];        // [128-byte half of the row]
-  u32x4 v[2];        // [e - 2w]
+  u32x4 k[8 / W];    // [pair - first pair][128-byte half of the row]
+  u32x4 v[8 / W];    // [e - first e]
 };
-template <bool NT>
-__device__ __forceinline__ void load_part(PartRegs& pr, const char* kt, const char* vt,
+template <bool NT, int W>
+__device__ __forceinline__ void load_part(PartRegs<W>& pr, const char* kt, const char* vt,
                                           uint32_t row_bytes, int rows, const LaneGeom& lg, int w) {
   const int top = rows - 1;
-  int r = lg.krow + 16 * (w >> 1) + 2 * (w & 1);
-  r = r < top ? r : top;
-  const uint32_t off = __umul24((uint32_t)r, row_bytes) + lg.kcol;
 #pragma unroll
-  for (int half = 0; half < 2; ++half) pr.k[half] = stream_load_at<NT>(kt, off + 128 * half);
+  for (int j = 0; j < 4 / W; ++j) {
+    const int pair = w * (4 / W) + j;
+    int r = lg.krow + 16 * (pair >> 1) + 2 * (pair & 1);
+    r = r < top ? r : top;
+    const uint32_t off = __umul24((uint32_t)r, row_bytes) + lg.kcol;
 #pragma unroll
-  for (int j = 0; j < 2; ++j) {
-    const int e = 2 * w + j;
+    for (int half = 0; half < 2; ++half) pr.k[2 * j + half] = stream_load_at<NT>(kt, off + 128 * half);
+  }
+#pragma unroll
+  for (int j = 0; j < 8 / W; ++j) {
+    const int e = w * (8 / W) + j;
     int rv = lg.vrow + 16 * (e >> 2) + 4 * (e & 3);
     rv = rv < top ? rv : top;
     pr.v[j] = stream_load_at<NT>(vt, __umul24((uint32_t)rv, row_bytes) + lg.vcol);
   }
 }
-// The tile the four waves put together in LDS: the 32 K rows and the 32 V rows as they lie in the
+// The tile the waves of a workgroup put together in LDS: the 32 K rows and the 32 V rows as they lie in the
 // cache, 256 bytes each, at a pitch of 272 bytes -- so that the 16 rows a 16-lane group reads at
 // the same byte column fall into 16 different groups of four banks.
 constexpr int kLdsPitch = 272;
@@ -170,23 +175,24 @@ struct __attribute__((aligned(16))) TileLds {
   char k[32 * kLdsPitch];
   char v[32 * kLdsPitch];
 };
-__device__ __forceinline__ void put_part(TileLds& x, const PartRegs& pr, int w, const LaneGeom& lg) {
-  const int rk = lg.krow + 16 * (w >> 1) + 2 * (w & 1);
+template <int W>
+__device__ __forceinline__ void put_part(TileLds& x, const PartRegs<W>& pr, int w, const LaneGeom& lg) {
 #pragma unroll
-  for (int half = 0; half < 2; ++half)
-    *reinterpret_cast<u32x4*>(x.k + rk * kLdsPitch + lg.kcol + 128 * half) = pr.k[half];
+  for (int j = 0; j < 4 / W; ++j) {
+    const int pair = w * (4 / W) + j;
+    const int rk = lg.krow + 16 * (pair >> 1) + 2 * (pair & 1);
 #pragma unroll
-  for (int j = 0; j < 2; ++j) {
-    const int e = 2 * w + j;
+    for (int half = 0; half < 2; ++half)
+      *reinterpret_cast<u32x4*>(x.k + rk * kLdsPitch + lg.kcol + 128 * half) = pr.k[2 * j + half];
+  }
+#pragma unroll
+  for (int j = 0; j < 8 / W; ++j) {
+    const int e = w * (8 / W) + j;
     const int rv = lg.vrow + 16 * (e >> 2) + 4 * (e & 3);
     *reinterpret_cast<u32x4*>(x.v + rv * kLdsPitch + lg.vcol) = pr.v[j];
   }
 }
 
-// One 32-row tile for P passes of 16 head columns each (own Q operand, running state and
-// accumulators per pass; the K operands and the transposed V operands are built once).  `lim` is
-// the number of rows the lane's head column attends (rows at or beyond it are masked); columns of
-// one tile may have different limits, and a column may have no row at all in a tile.
 // The online-softmax update of one tile for P passes: from the raw scores s (register e = 4T + i of
 // lane (hn, c) is head column hn against tile row 16T + 4i + c) to the probabilities as two 16-bit
 // operands (hi + lo), with the running exponent m and sum l brought up to date and the accumulators
@@ -201,23 +207,20 @@ __device__ __forceinline__ void softmax_tile(const f32x4 (&s)[P][2], u32x4 (&p_h
 #pragma unroll
   for (int i = 0; i < P; ++i) {
     float tv[8];
-    float mx = kNegInf;
+#pragma unroll
+    for (int e = 0; e < 8; ++e) tv[e] = s[i][e >> 2][e & 3] * scale_log2e;
     // rows at or beyond the column's limit are masked (select, not multiply: what lies there may
     // be anything); a tile that every column of the wave attends in full skips the selects
-    if (__all(tile_row0 + 32 <= lim[i])) {
-#pragma unroll
-      for (int e = 0; e < 8; ++e) {
-        tv[e] = s[i][e >> 2][e & 3] * scale_log2e;
-        mx = fmaxf(mx, tv[e]);
-      }
-    } else {
+    if (!__all(tile_row0 + 32 <= lim[i])) {
 #pragma unroll
       for (int e = 0; e < 8; ++e) {
         const int row = tile_row0 + 16 * (e >> 2) + 4 * (e & 3) + c;
-        tv[e] = row < lim[i] ? s[i][e >> 2][e & 3] * scale_log2e : kNegInf;
-        mx = fmaxf(mx, tv[e]);
+        tv[e] = row < lim[i] ? tv[e] : kNegInf;
       }
     }
+    float mx = kNegInf;
+#pragma unroll
+    for (int e = 0; e < 8; ++e) mx = fmaxf(mx, tv[e]);
     mx = rows_max(mx);
     // m is the exponent the column's running sums are scaled by.  It follows the running maximum
     // lazily: the sums are rescaled only when the maximum has grown by more than kLazyExponent
@@ -813,14 +816,16 @@ struct TileCursor {
 // P = passes of 16 head columns a wave carries through a strip at once (own Q operand, running
 // state and accumulators per pass, one stream of tiles for all): 1 for decode, 2 for token groups
 // with more than 16 head columns, at one wave per SIMD instead of two.
-// COOP: the four waves of a workgroup are one worker: they walk the same tiles, each with its own P
-//       passes, fetch a quarter of every tile each and hand the quarters to one another through LDS.
+// COOP: 0, or the number of waves (2 or 4) of a workgroup that is one worker: its waves walk the
+//       same tiles, each with its own P passes, fetch a share of every tile each, put the tile
+//       together in LDS and read their operands from there.
 // FUSED: the whole step in one launch (see AttnArgs): append, attention and merge.
-template <bool BF16, bool GROUPED, int P, bool COOP, bool FUSED>
-__global__ __launch_bounds__(256, COOP || P == 1 ? 2 : 1) void attn_mfma_balanced_kernel(const AttnArgs a) {
+template <bool BF16, bool GROUPED, int P, int COOP, bool FUSED>
+__global__ __launch_bounds__(COOP ? 64 * COOP : 256, COOP || P == 1 ? 2 : 1)
+void attn_mfma_balanced_kernel(const AttnArgs a) {
   static_assert(!(FUSED && GROUPED), "the one-launch step is for batches of one token per slot");
   static_assert(!(FUSED && COOP), "the one-launch step runs a wave per worker");
-  constexpr int kThreads = 256;
+  constexpr int kThreads = COOP ? 64 * COOP : 256;
   extern __shared__ uint32_t lds[];
   __shared__ uint32_t part[kThreads];
   const int tid = threadIdx.x;
@@ -883,10 +888,10 @@ __global__ __launch_bounds__(256, COOP || P == 1 ? 2 : 1) void attn_mfma_balance
   const uint32_t total = uni(cum[B]);
   const int lane = tid & 63;
   const int hn = lane & 15, c = lane >> 4;
-  // Worker: one wave, or (COOP) the four waves of the workgroup, which walk the same tiles, each
+  // Worker: one wave, or (COOP) the waves of the workgroup, which walk the same tiles, each
   // with its own passes; gw numbers the workers.
   const uint32_t wave = uni(tid >> 6);
-  constexpr uint32_t n_share = COOP ? 4u : 1u;
+  constexpr uint32_t n_share = COOP ? (uint32_t)COOP : 1u;
   const uint32_t gw = COOP ? blockIdx.x : blockIdx.x * 4 + wave;
   const int wsub = COOP ? (int)wave * P : 0;                   // first pass of this wave in a strip's set
   uint32_t share = (total + a.n_workers - 1) / a.n_workers;    // tiles per worker
@@ -992,11 +997,12 @@ __global__ __launch_bounds__(256, COOP || P == 1 ? 2 : 1) void attn_mfma_balance
     tile_source(cu, kt, vt, rows);
     load_tile<true>(regs, kt, vt, row_bytes, rows, lg);
   };
-  auto issue_part = [&](PartRegs& pr, const TileCursor& cu) {
+  constexpr int kPartWaves = COOP ? COOP : 4;
+  auto issue_part = [&](PartRegs<kPartWaves>& pr, const TileCursor& cu) {
     const char *kt, *vt;
     int rows;
     tile_source(cu, kt, vt, rows);
-    load_part<true>(pr, kt, vt, row_bytes, rows, lg, (int)wave);
+    load_part<true, kPartWaves>(pr, kt, vt, row_bytes, rows, lg, (int)wave);
   };
 
   // cursor of the tile being computed; start: largest b with cum[b] <= t0
@@ -1209,30 +1215,30 @@ __global__ __launch_bounds__(256, COOP || P == 1 ? 2 : 1) void attn_mfma_balance
   };
 
   if constexpr (COOP) {
-    // Each wave keeps its quarters of the next two tiles in flight (four were measured: no faster,
-    // and two leave the registers for two workgroups per compute unit).  Per tile: put the quarter
-    // that has arrived into the LDS tile, ask for the quarter two tiles on, meet the other waves,
+    // Each wave keeps its shares of the next two tiles in flight (four were measured: no faster, and
+    // two leave the registers for two waves per SIMD).  Per tile: put the share that has arrived
+    // into the LDS tile, ask for the share two tiles on, meet the other waves,
     // compute from LDS.  Two LDS tiles and one barrier per tile: the tile written before
     // barrier i is read after it, and is written again only after barrier i + 1, which no wave
-    // passes before all have finished reading.  The four waves run the same tiles to the same end,
+    // passes before all have finished reading.  The waves run the same tiles to the same end,
     // so every wave reaches every barrier.
     __shared__ TileLds exchange[2];
-    auto next_part = [&](PartRegs& pr) {
+    auto next_part = [&](PartRegs<kPartWaves>& pr) {
       if (ld.t + 1 < t_end) advance(ld);
       issue_part(pr, ld);
     };
-    PartRegs p0, p1;
+    PartRegs<kPartWaves> p0, p1;
     issue_part(p0, ld);
     next_part(p1);
     int buf = 0;
-    // (Steps come two to a loop iteration, one per register quarter, and the loop has a single
+    // (Steps come two to a loop iteration, one per register share, and the loop has a single
     // exit: a step past the worker's last tile still puts, loads -- the last position again -- and
     // meets the others, and skips the arithmetic.  With an exit after every step the paths that
     // leave would join the loop's back edge, and the wait before the first put of an iteration
-    // would be for everything in flight instead of for that quarter.)
+    // would be for everything in flight instead of for that share.)
     bool live = true;
-    auto step = [&](PartRegs& pr) {
-      put_part(exchange[buf], pr, (int)wave, lg);
+    auto step = [&](PartRegs<kPartWaves>& pr) {
+      put_part<kPartWaves>(exchange[buf], pr, (int)wave, lg);
       next_part(pr);
       __syncthreads();
       if (live) {

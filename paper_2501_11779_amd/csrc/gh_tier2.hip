@@ -21,31 +21,32 @@ namespace {
 using namespace gh_plan;
 
 // Instantiations of the balanced kernel: dtype x (token groups) x (one | two passes per wave) x
-// (a wave per worker | the workgroup's four waves as one worker).
+// (a wave per worker | a workgroup of four waves as one worker; the kernel also takes two, which
+// was measured on groups of 17 to 32 head columns and is no faster than two passes per wave).
 template <bool BF16, bool GROUPED, bool FUSED>
-void launch_balanced_as(const gh::AttnArgs& a, int passes, bool coop, size_t lds, hipStream_t s) {
-  const dim3 grid(coop ? a.n_workers : a.n_workers / 4), block(256);
-  if (passes == 1 && !coop)
-    hipLaunchKernelGGL((gh::attn_mfma_balanced_kernel<BF16, GROUPED, 1, false, FUSED>), grid, block, lds, s, a);
-  else if (passes == 2 && !coop)
-    hipLaunchKernelGGL((gh::attn_mfma_balanced_kernel<BF16, GROUPED, 2, false, FUSED>), grid, block, lds, s, a);
+void launch_balanced_as(const gh::AttnArgs& a, int passes, int share, size_t lds, hipStream_t s) {
+  const dim3 grid(share > 1 ? a.n_workers : a.n_workers / 4), block(share > 1 ? 64 * share : 256);
+  if (passes == 1 && share == 1)
+    hipLaunchKernelGGL((gh::attn_mfma_balanced_kernel<BF16, GROUPED, 1, 0, FUSED>), grid, block, lds, s, a);
+  else if (passes == 2 && share == 1)
+    hipLaunchKernelGGL((gh::attn_mfma_balanced_kernel<BF16, GROUPED, 2, 0, FUSED>), grid, block, lds, s, a);
   else if constexpr (!FUSED) {         // (the caller keeps the one-launch step off cooperative plans)
     if (passes == 1)
-      hipLaunchKernelGGL((gh::attn_mfma_balanced_kernel<BF16, GROUPED, 1, true, false>), grid, block, lds, s, a);
+      hipLaunchKernelGGL((gh::attn_mfma_balanced_kernel<BF16, GROUPED, 1, 4, false>), grid, block, lds, s, a);
     else
-      hipLaunchKernelGGL((gh::attn_mfma_balanced_kernel<BF16, GROUPED, 2, true, false>), grid, block, lds, s, a);
+      hipLaunchKernelGGL((gh::attn_mfma_balanced_kernel<BF16, GROUPED, 2, 4, false>), grid, block, lds, s, a);
   }
 }
 // fused: the one-launch step (never with token groups)
 void launch_balanced(const gh::AttnArgs& a, bool bf16, bool grouped, bool fused, int passes,
-                     bool coop, size_t lds, hipStream_t s) {
+                     int share, size_t lds, hipStream_t s) {
   if (fused) {
-    if (bf16) launch_balanced_as<true, false, true>(a, passes, coop, lds, s);
-    else launch_balanced_as<false, false, true>(a, passes, coop, lds, s);
-  } else if (bf16 && grouped) launch_balanced_as<true, true, false>(a, passes, coop, lds, s);
-  else if (bf16) launch_balanced_as<true, false, false>(a, passes, coop, lds, s);
-  else if (grouped) launch_balanced_as<false, true, false>(a, passes, coop, lds, s);
-  else launch_balanced_as<false, false, false>(a, passes, coop, lds, s);
+    if (bf16) launch_balanced_as<true, false, true>(a, passes, share, lds, s);
+    else launch_balanced_as<false, false, true>(a, passes, share, lds, s);
+  } else if (bf16 && grouped) launch_balanced_as<true, true, false>(a, passes, share, lds, s);
+  else if (bf16) launch_balanced_as<true, false, false>(a, passes, share, lds, s);
+  else if (grouped) launch_balanced_as<false, true, false>(a, passes, share, lds, s);
+  else launch_balanced_as<false, false, false>(a, passes, share, lds, s);
 }
 
 template <bool BF16>
@@ -231,7 +232,7 @@ int32_t launch_attention(const gh_problem* p, const void* q, const void* k_cache
     // (the one-launch step runs a wave per worker; with cooperative workers gh_decode_step takes
     // the three-kernel route, and this launch only reads positions instead of lengths)
     launch_balanced(a, bf16, a.tokens > 1, step.k_new != nullptr && pl.share == 1,
-                    pl.passes_per_strip, pl.share > 1, lds, s);
+                    pl.passes_per_strip, pl.share, lds, s);
   } else if (pl.kernel == GH_KERNEL_MFMA) {
     const dim3 grid(a.n_items), block(64);
     if (bf16)
