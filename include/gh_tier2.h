@@ -60,8 +60,8 @@
  *     padded with ctx_len = 0 rows and a decode entry is a group with one live
  *     row.  Results are those of the undeclared batch up to fp32 rounding
  *     order.  gh_kv_append and the merge are unaffected (they work per row).
- *     Requires the matrix-core kernel with the library's split (chunk_rows = 0,
- *     at most 4096 groups); anything else returns GH_ERR_UNSUPPORTED.
+ *     Requires the matrix-core kernel with the library's split (chunk_rows =
+ *     0); anything else returns GH_ERR_UNSUPPORTED.
  */
 #ifndef GH_TIER2_H
 #define GH_TIER2_H
@@ -144,8 +144,9 @@ const char* gh_status_string(int32_t status);
  * Fixed split (chunk_rows > 0, and always for GH_KERNEL_VALU, where 0 lets the
  * library pick the chunk size): record c of a head covers rows
  * [c*chunk_rows, (c+1)*chunk_rows) of its sequence.
- * Balanced split (chunk_rows == 0 with the MFMA kernel, batch <= 4096): the
- * rows of the whole batch are cut into equal shares, one per resident wave;
+ * Balanced split (chunk_rows == 0 with the MFMA kernel): the rows of the whole
+ * batch -- of each slice of 4096 sequences, if it has more -- are cut into
+ * equal shares, one per resident wave;
  * the non-empty records of a head cover consecutive row ranges that partition
  * [0, ctx_len) but whose borders depend on the other sequences' lengths.
  *
@@ -198,6 +199,9 @@ typedef struct {
   int32_t waves_per_worker;   /* 1 or 4: the waves of a worker walk the same
                                  tiles, each with its own passes_per_strip passes
                                  (a strip then stands for their product of passes) */
+  int32_t groups_per_launch;  /* a batch of more groups is launched in slices of
+                                 this many (4096), each split as described, on
+                                 its own                                          */
 } gh_split_plan;
 int32_t gh_decode_split_plan(const gh_problem* p, gh_split_plan* out);
 
@@ -297,9 +301,9 @@ int32_t gh_decode_reduce_native(const gh_problem* p, const void* workspace,
  *     them zero again.  Two steps that overlap in time need two workspaces.
  *   - out / out_kind as for gh_decode_attention_out; every row of `out` is
  *     written.  Deterministic for given inputs (fixed summation order).
- *   - With a fixed split (chunk_rows > 0), GH_KERNEL_VALU, a batch beyond the
- *     balanced split or more than 32 query heads per kv head the call issues
- *     the three kernels instead, same result.
+ *   - With a fixed split (chunk_rows > 0), GH_KERNEL_VALU or more than 32 query
+ *     heads per kv head the call issues the three kernels instead, same result.
+ *     A batch of more than 4096 sequences is issued in slices of 4096.
  *   - kernel = GH_KERNEL_STRIPS (with chunk_rows = 0): one workgroup per strip,
  *     see gh_kernel; the workspace is then not touched.
  */

@@ -49,7 +49,8 @@ class gh_problem(C.Structure):
 class gh_split_plan(C.Structure):
     _fields_ = [("balanced", C.c_int32), ("n_workers", C.c_int32), ("min_share", C.c_int32),
                 ("passes_per_strip", C.c_int32), ("strips_per_kv_head", C.c_int32),
-                ("n_chunks", C.c_int32), ("waves_per_worker", C.c_int32)]
+                ("n_chunks", C.c_int32), ("waves_per_worker", C.c_int32),
+                ("groups_per_launch", C.c_int32)]
 
 
 class gh_slot_pool_config(C.Structure):

@@ -33,7 +33,7 @@ struct AttnArgs {
   int32_t n_items;                                // B * H_kv * n_pass * n_chunks (fixed split)
   int32_t batch;
   int32_t n_workers, min_share;                   // balanced split: workers, least tiles per worker
-  int32_t share;                                  // balanced split: waves per worker (1, 2 or 4)
+  int32_t share;                                  // balanced split: waves per worker (1, or 4: a workgroup)
   float scale_log2e;                              // scale * log2(e)
   void* out;                                      // final results of heads one wave covers alone
   int32_t out_kind;                               // 0 none, 1 fp32, 2 binary16, 3 bfloat16

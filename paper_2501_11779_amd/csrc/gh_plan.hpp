@@ -34,7 +34,9 @@ inline void block_params(const gh_problem* p, int64_t* stride, int32_t* shift, i
 
 inline bool aligned16(const void* p) { return (reinterpret_cast<uintptr_t>(p) & 15u) == 0; }
 
-constexpr int kBalancedMaxBatch = 4096;     // three per-group arrays live in LDS (48 KB)
+constexpr int kBalancedMaxBatch = 4096;     // groups per launch of the balanced split: three
+                                            // per-group arrays live in LDS (48 KB); a larger batch
+                                            // is launched in slices
 constexpr int kMaxTokensPerGroup = 64;
 
 inline int tokens_per_group(const gh_problem* p) { return p->tokens_per_group > 1 ? p->tokens_per_group : 1; }
@@ -66,7 +68,7 @@ inline int32_t check_problem(const gh_problem* p) {
     // groups run on the matrix-core kernel with the library's split only
     if (p->batch % p->tokens_per_group != 0) return GH_ERR_SHAPE;
     if (p->tokens_per_group > kMaxTokensPerGroup || p->kernel == GH_KERNEL_VALU ||
-        p->chunk_rows != 0 || p->batch / p->tokens_per_group > kBalancedMaxBatch)
+        p->chunk_rows != 0)
       return GH_ERR_UNSUPPORTED;
   }
   if (p->q_batch_stride < 0 || p->new_batch_stride < 0) return GH_ERR_SHAPE;
@@ -124,6 +126,8 @@ struct Plan {
   int share;                // balanced split: waves per worker (1, or 4: a whole workgroup); the
                             // waves of a worker walk the same tiles, each with its own
                             // passes_per_strip passes
+  int launch_groups;        // balanced split: groups per launch (the batch goes in slices of
+                            // this many groups, each split on its own)
 };
 
 constexpr int kBalancedWavesPerCU = 8;      // resident waves of the MFMA kernel per compute unit
@@ -137,7 +141,9 @@ inline Plan make_plan(const gh_problem* p) {
   pl.n_workers = pl.min_share = 0;
   pl.passes_per_strip = 1;
   pl.share = 1;
-  const int groups = p->batch / tokens_per_group(p);
+  pl.launch_groups = 0;
+  const int all_groups = p->batch / tokens_per_group(p);
+  const int groups = all_groups < kBalancedMaxBatch ? all_groups : kBalancedMaxBatch;   // of one launch
   // Head columns per kv head (a head group, or a token group's heads) in passes of 16:
   //   up to 16: a wave carries one pass, two waves per SIMD;
   //   up to 32: a wave carries two passes through one stream of tiles, at one wave per SIMD (the
@@ -154,14 +160,14 @@ inline Plan make_plan(const gh_problem* p) {
   const int64_t strips = (int64_t)(groups > 0 ? groups : 1) * p->n_kv_heads * n_strip;
   // (+ 1: the one-launch step walks the appended row as a tile of its own behind the cached rows)
   const int64_t max_tiles = (p->max_ctx_len > 0 ? (p->max_ctx_len + 31) / 32 : 1) + 1;
-  if (pl.kernel == GH_KERNEL_MFMA && p->chunk_rows == 0 && groups <= kBalancedMaxBatch &&
-      strips * max_tiles < 0x7fffffff) {
+  if (pl.kernel == GH_KERNEL_MFMA && p->chunk_rows == 0 && strips * max_tiles < 0x7fffffff) {
     // Records per head: enough for the longest strip when strips are up to four times the
     // average length; beyond that the share per wave grows instead (min_share).
     pl.balanced = true;
     pl.passes_per_strip = pps;
     pl.n_pass = n_strip;
     pl.share = share;
+    pl.launch_groups = groups > 0 ? groups : 1;
     // workers: a wave each, as many as are resident (eight per compute unit with one pass, four
     // with two); or a workgroup each, two per compute unit
     pl.n_workers = share == 4 ? kComputeUnits * 2

@@ -104,6 +104,7 @@ int32_t gh_decode_split_plan(const gh_problem* p, gh_split_plan* out) {
     out->passes_per_strip = pl.passes_per_strip;
     out->strips_per_kv_head = pl.n_pass;
     out->waves_per_worker = pl.share;
+    out->groups_per_launch = pl.launch_groups;
   }
   return GH_OK;
 }
@@ -228,11 +229,34 @@ int32_t launch_attention(const gh_problem* p, const void* q, const void* k_cache
   hipStream_t s = static_cast<hipStream_t>(hip_stream);
   const bool bf16 = p->dtype == GH_BF16;
   if (pl.balanced) {
-    const size_t lds = (size_t)(3 * a.batch + 1) * sizeof(uint32_t);
-    // (the one-launch step runs a wave per worker; with cooperative workers gh_decode_step takes
-    // the three-kernel route, and this launch only reads positions instead of lengths)
-    launch_balanced(a, bf16, a.tokens > 1, step.k_new != nullptr && pl.share == 1,
-                    pl.passes_per_strip, pl.share, lds, s);
+    // A batch of more groups than one launch takes goes in slices, each split on its own: every
+    // per-entry array moves on by the slice's entries (the kernels index them from their bases).
+    const int64_t groups = a.batch;
+    const size_t esize = a.out_kind == 1 ? 4 : 2;
+    for (int64_t g0 = 0; g0 < groups; g0 += pl.launch_groups) {
+      gh::AttnArgs b = a;
+      const int64_t e0 = g0 * a.tokens;                          // first batch entry of the slice
+      b.batch = (int32_t)(groups - g0 < pl.launch_groups ? groups - g0 : pl.launch_groups);
+      b.q = a.q + e0 * a.q_batch_stride;
+      b.slot_id = a.slot_id + e0;
+      b.ctx_len = a.ctx_len + e0;
+      const int64_t h0 = e0 * p->n_q_heads;                      // first (entry, head) pair
+      b.ws_o = a.ws_o + h0 * pl.n_chunks * gh::kHeadDim;
+      b.ws_m = a.ws_m + h0 * pl.n_chunks;
+      b.ws_l = a.ws_l + h0 * pl.n_chunks;
+      b.ws_n = a.ws_n + h0;
+      b.arrive = a.arrive + h0;
+      if (a.k_new) {
+        b.k_new = a.k_new + e0 * a.new_batch_stride;
+        b.v_new = a.v_new + e0 * a.new_batch_stride;
+      }
+      if (a.out) b.out = static_cast<char*>(a.out) + h0 * gh::kHeadDim * esize;
+      const size_t lds = (size_t)(3 * b.batch + 1) * sizeof(uint32_t);
+      // (the one-launch step runs a wave per worker; with cooperative workers gh_decode_step
+      // takes the three-kernel route, and this launch only reads positions instead of lengths)
+      launch_balanced(b, bf16, a.tokens > 1, step.k_new != nullptr && pl.share == 1,
+                      pl.passes_per_strip, pl.share, lds, s);
+    }
   } else if (pl.kernel == GH_KERNEL_MFMA) {
     const dim3 grid(a.n_items), block(64);
     if (bf16)

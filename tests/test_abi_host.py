@@ -269,6 +269,11 @@ def test_split_plan_reports_the_fixed_split_and_checks_its_arguments():
     # 64 tokens: 512 columns = four such strips; 3 passes: four waves of one pass, the last without columns
     assert G.gh_decode_split_plan(good(batch=64, tokens_per_group=64, n_q_heads=64, n_kv_heads=8)
                                   ).strips_per_kv_head == 4
+    assert four.groups_per_launch == 4                     # 64 entries are four groups of 16
+    # a batch beyond one launch goes in slices of 4096 groups; the numbers are those of a slice
+    big = G.gh_decode_split_plan(good(batch=10000, n_slots=10000))
+    assert big.balanced == 1 and big.groups_per_launch == 4096
+    assert big.n_chunks == G.gh_decode_split_plan(good(batch=4096, n_slots=4096)).n_chunks
     three = G.gh_decode_split_plan(good(n_q_heads=40, n_kv_heads=1, strides=(4097 * 128, 4097 * 128, 128)))
     assert (three.passes_per_strip, three.waves_per_worker, three.strips_per_kv_head, three.n_workers) \
         == (1, 4, 1, 512)

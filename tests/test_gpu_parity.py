@@ -152,15 +152,36 @@ def test_rows_padded_to_twice_the_head_dim(kernel):
     assert np.array_equal(W.bits(wide["v_cache"]), host["v_cache"])
 
 
-def test_batch_above_the_balanced_split_limit_uses_the_fixed_split():
-    """More than 4096 sequences: the library falls back to fixed chunks for the MFMA kernel."""
-    B = 4100
+@pytest.mark.parametrize("B", [4100, 8200])
+def test_batch_above_one_launch_of_the_balanced_split_goes_in_slices(B):
+    """More than 4096 sequences: the balanced split is launched on slices of 4096, each split on
+    its own (a slice of four sequences; two full slices and a short one)."""
     w = W.Workload("big", B, 4, 2, 128, "f16", ("uniform", 0, 150), 52)
     inp = W.make_inputs(w, DEV)
     host = Hh.host_copy(inp)
     got, p, _ = run_gpu(inp, 0, G.GH_KERNEL_MFMA)
-    assert G.gh_decode_chunk_rows(p) > 0
-    Hh.assert_parity(got, Hh.oracle_step(inp, host), "B=4100")
+    plan = G.gh_decode_split_plan(p)
+    assert G.gh_decode_chunk_rows(p) == 0 and plan.balanced == 1 and plan.groups_per_launch == 4096
+    Hh.assert_tight(got, Hh.oracle_step(inp, host), f"B={B}")
+
+
+def test_token_groups_above_one_launch_go_in_slices():
+    """4100 groups of two tokens: the slices are cut at group borders."""
+    T, groups = 2, 4100
+    w = W.Workload("biggroups", groups * T, 4, 2, 128, "bf16", ("const", 0), 58)
+    rng = np.random.default_rng(58)
+    base = rng.integers(0, 60, size=groups)
+    lengths = (np.repeat(base, T) + np.tile(np.arange(T), groups)).astype(np.int32)
+    slots = np.repeat(rng.permutation(groups), T).astype(np.int32)
+    inp = W.make_inputs(w, DEV, lengths=lengths, slots=slots, n_slots=groups)
+    host = Hh.host_copy(inp)
+    p = G.problem_from_inputs(inp, tokens_per_group=T)
+    ws = G.alloc_workspace(p, DEV)
+    out = torch.empty((w.batch, w.n_q_heads, w.head_dim), dtype=torch.float32, device=DEV)
+    G.decode_step(p, inp, ws, out)
+    torch.cuda.synchronize()
+    assert G.gh_decode_split_plan(p).groups_per_launch == 4096
+    Hh.assert_tight(out.cpu().numpy(), Hh.oracle_step(inp, host), "4100 groups")
 
 
 @pytest.mark.parametrize("kernel", ["valu", "mfma"])

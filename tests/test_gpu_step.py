@@ -8,6 +8,7 @@ import numpy as np
 import pytest
 import torch
 
+from oracle import gh_oracle as O
 from paper_2501_11779_amd import binding as G
 from paper_2501_11779_amd import workloads as W
 from tests import helpers as Hh
@@ -151,22 +152,41 @@ def test_one_launch_step_with_the_16_bit_result(dtype):
     assert same > 0.995
 
 
-@pytest.mark.parametrize("how", ["fixed_split", "valu", "large_batch"])
+@pytest.mark.parametrize("how", ["fixed_split", "valu"])
 def test_the_three_kernel_route_of_the_step_call_gives_the_same(how):
     """Where the one-launch kernel does not apply the call issues append, attention and merge."""
-    if how == "large_batch":
-        w = W.Workload("stepbig", 4100, 4, 2, 128, "bf16", ("uniform", 0, 40), 164)
-        inp = W.make_inputs(w, DEV)
-        chunk_rows, kernel = 0, G.GH_KERNEL_AUTO
-    else:
-        w = W.Workload("stepfix", len(RAGGED), 8, 2, 128, "f16", ("const", 0), 165)
-        inp = W.make_inputs(w, DEV, lengths=RAGGED)
-        chunk_rows, kernel = (128, G.GH_KERNEL_MFMA) if how == "fixed_split" else (0, G.GH_KERNEL_VALU)
+    w = W.Workload("stepfix", len(RAGGED), 8, 2, 128, "f16", ("const", 0), 165)
+    inp = W.make_inputs(w, DEV, lengths=RAGGED)
+    chunk_rows, kernel = (128, G.GH_KERNEL_MFMA) if how == "fixed_split" else (0, G.GH_KERNEL_VALU)
     host = Hh.host_copy(inp)
     status = torch.zeros(1, dtype=torch.int32, device=DEV)
     out, p, _ = run_step(inp, chunk_rows, kernel, status=status)
     assert G.gh_decode_split_plan(p).balanced == 0 and int(status.item()) == 0
     Hh.assert_tight(out.cpu().numpy(), Hh.oracle_step(inp, host), how)
+    assert np.array_equal(W.bits(inp["k_cache"]), host["k_cache"])
+    assert np.array_equal(W.bits(inp["v_cache"]), host["v_cache"])
+
+
+def test_one_launch_step_on_a_batch_of_more_than_one_slice():
+    """4100 sequences: the one launch becomes two, the second on the last four sequences; a bad
+    position in the second slice is skipped and flagged like anywhere else."""
+    w = W.Workload("stepbig", 4100, 4, 2, 128, "bf16", ("uniform", 0, 40), 164)
+    inp = W.make_inputs(w, DEV)
+    inp["pos"][4098] = inp["capacity"] + 5
+    inp["ctx_len"][4098] = 0                                 # (what the oracle attends for it)
+    host = Hh.host_copy(inp)
+    status = torch.zeros(1, dtype=torch.int32, device=DEV)
+    out, p, _ = run_step(inp, 0, G.GH_KERNEL_AUTO, status=status)
+    plan = G.gh_decode_split_plan(p)
+    assert plan.balanced == 1 and plan.groups_per_launch == 4096 and int(status.item()) == 2
+    po = Hh.oracle_problem(inp)
+    assert O.kv_append(po, host["k_cache"], host["v_cache"], host["k_new"], host["v_new"],
+                       host["slot_id"], host["pos"]) == 1
+    want = O.decode_attention(po, host["q"], host["k_cache"], host["v_cache"], host["slot_id"],
+                              host["ctx_len"])
+    got = out.cpu().numpy()
+    assert not got[4098].any()
+    Hh.assert_tight(got, want, "4100 sequences in one call")
     assert np.array_equal(W.bits(inp["k_cache"]), host["k_cache"])
     assert np.array_equal(W.bits(inp["v_cache"]), host["v_cache"])
 
