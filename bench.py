@@ -2,8 +2,10 @@
 """Benchmark of the Tier-2 attention step on one MI355X.
 
 A step is one pass of the whole hot path over one batch of synthetic input already resident
-in HBM: gh_kv_append -> gh_decode_attention -> gh_decode_reduce on one stream.  The same row is
-re-appended at the same position every step, so each step moves identical bytes.
+in HBM: gh_kv_append -> gh_decode_attention_out -> gh_decode_reduce on one stream (the attention
+kernel stores the final rows of the heads whose strip one worker covered alone; the merge completes
+the others).  The same row is re-appended at the same position every step, so each step moves
+identical bytes.
 
 Prints ONE JSON line on stdout (diagnostics go to stderr):
   value     sequence-steps per second over the timed steps (wall clock, sync on both sides)
@@ -23,10 +25,10 @@ if ROOT not in sys.path:
 
 HBM_PEAK_GBS = 8000.0   # MI355X published HBM3E peak
 
-# HBM bytes per gh_decode_attention launch (FETCH_SIZE + WRITE_SIZE, each scaled by what the same
-# counter reads for a plain 1 GiB device copy) are read from profiles/traffic.json, which
-# `python -m paper_2501_11779_amd.profile` writes together with the rocprofv3 summaries in
-# profiles/; they are valid for the library's default kernel and split only.
+# HBM bytes per attention launch (FETCH_SIZE + WRITE_SIZE, each scaled by what the same counter
+# reads for a plain 1 GiB device copy) are read from profiles/traffic.json, which
+# `python -m paper_2501_11779_amd.rocprof_summary` writes together with the rocprofv3 summaries in
+# profiles/; they are valid for this file's default step only.
 TRAFFIC_FILE = os.path.join(ROOT, "profiles", "traffic.json")
 
 
@@ -138,8 +140,8 @@ def time_default_step(name, steps, warmup, keep):
                                inp["slot_id"], inp["pos"], None))
         if ev is not None:
             ev[0].record()
-        G.check(G.gh_decode_attention(p, inp["q"], inp["k_cache"], inp["v_cache"], inp["slot_id"],
-                                      inp["ctx_len"], ws))
+        G.check(G.gh_decode_attention_out(p, inp["q"], inp["k_cache"], inp["v_cache"], inp["slot_id"],
+                                          inp["ctx_len"], ws, out, G.GH_OUT_F32))
         if ev is not None:
             ev[1].record()
         G.check(G.gh_decode_reduce(p, ws, inp["ctx_len"], out))
@@ -240,9 +242,10 @@ def main():
                          "the GB/s printed then counts every row's K/V as if read separately")
     ap.add_argument("--out16", action="store_true",
                     help="experiment: the merge stores the model's 16-bit type (gh_decode_reduce_native)")
-    ap.add_argument("--early", action="store_true",
-                    help="experiment: gh_decode_attention_out (the attention kernel stores the heads "
-                         "one wave covers alone; the merge completes the rest)")
+    ap.add_argument("--records-only", action="store_true",
+                    help="gh_decode_attention instead of gh_decode_attention_out: every strip writes "
+                         "partial records, also where one worker covered it alone and could store "
+                         "the final rows (the default step stores those directly)")
     ap.add_argument("--one-launch", action="store_true",
                     help="time the step as one gh_decode_step launch (append + attention + merge "
                          "fused) instead of gh_kv_append + gh_decode_attention + gh_decode_reduce")
@@ -367,7 +370,8 @@ def main():
 
     # gh_decode_step does not take batches whose entries share a slot (prefill chunks).
     one_launch = args.one_launch
-    assert not (one_launch and (args.mixed or args.prefill or args.group or args.early))
+    assert not (one_launch and (args.mixed or args.prefill or args.group))
+    early = not args.records_only
     if one_launch:
         G.check(G.gh_decode_step_init(p, ws))
 
@@ -386,7 +390,7 @@ def main():
                                inp["slot_id"], inp["pos"], None))
         if events is not None:
             events[0].record()
-        if args.early:
+        if early:
             G.check(G.gh_decode_attention_out(p, inp["q"], inp["k_cache"], inp["v_cache"],
                                               inp["slot_id"], inp["ctx_len"], ws, out,
                                               G.GH_OUT_NATIVE if args.out16 else G.GH_OUT_F32))
@@ -449,7 +453,7 @@ def main():
 
     plain = args.kernel == "auto" and not (
         args.one_launch or args.chunk_rows or args.batch or args.const_len or args.capacity or args.paged or args.mixed
-        or args.prefill or args.group or args.out16 or args.early)
+        or args.prefill or args.group or args.out16 or args.records_only)
     traffic, traffic_source = (args.traffic_bytes, "command line") if args.traffic_bytes is not None \
         else measured_traffic(w.name) if plain else (None, None)
     result = {
@@ -465,7 +469,7 @@ def main():
                                f"seed={w.seed}",
                    "kernel": args.kernel, "chunk_rows": chunk_rows, "n_chunks": n_chunks,
                    "step": ("gh_decode_step (append + attention + merge in one launch)" if one_launch
-                            else "gh_kv_append + gh_decode_attention" + ("_out" if args.early else "")
+                            else "gh_kv_append + gh_decode_attention" + ("_out" if early else "")
                             + " + " + ("gh_decode_reduce_native" if args.out16 else "gh_decode_reduce")),
                    "paged_slots": paged_info, "hip_graph_ms_per_step": graph_ms,
                    "step_algorithmic_bytes": step_bytes,
@@ -474,7 +478,8 @@ def main():
                    "attention_ms_median": float(np.median(attn_ms)),
                    "attention_ms_min": float(attn_ms.min()),
                    "reduce_ms": float(red_ms.mean())},
-        "roofline": {"bound": "hbm", "kernel": "gh_decode_step" if one_launch else "gh_decode_attention",
+        "roofline": {"bound": "hbm", "kernel": "gh_decode_step" if one_launch else
+                     "gh_decode_attention_out" if early else "gh_decode_attention",
                      "achieved": achieved, "peak": HBM_PEAK_GBS, "unit": "GB/s",
                      "frac": achieved / HBM_PEAK_GBS,
                      "traffic": traffic, "traffic_source": traffic_source,
