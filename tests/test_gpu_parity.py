@@ -443,11 +443,11 @@ def test_seeded_sweep_of_token_groups():
         assert np.array_equal(W.bits(inp["k_cache"]), host["k_cache"])
 
 
+@pytest.mark.parametrize("T", [4, 16])       # 16 columns per kv head; 64: a workgroup per worker
 @pytest.mark.parametrize("layout", ["token_major", "head_blocked"])
-def test_token_groups_on_other_cache_layouts(layout):
+def test_token_groups_on_other_cache_layouts(layout, T):
     """Grouping and addressing are independent: the same grouped batch on a token-major and on a
     head-blocked cache (blocks of 32 rows, so every chunk crosses block borders)."""
-    T = 4
     rows = _grouped_rows(T)
     lengths = np.array([r[0] for r in rows], dtype=np.int32)
     slots = np.array([r[1] for r in rows], dtype=np.int32)
@@ -661,7 +661,7 @@ def test_seeded_sweep_of_shapes_layouts_and_splits():
 
 # ------------------------------------------------------------------ heads finished by the attention kernel
 @pytest.mark.parametrize("native", [False, True])
-@pytest.mark.parametrize("case", ["ragged", "groups", "large"])
+@pytest.mark.parametrize("case", ["ragged", "groups", "large", "wide_groups", "many_heads"])
 def test_attention_out_plus_merge_is_bit_identical_to_attention_plus_merge(case, native):
     """gh_decode_attention_out stores the heads one wave covers alone and marks them; the merge
     completes the rest.  The pair must give the same bits as attention + merge, in fp32 and in the
@@ -673,15 +673,22 @@ def test_attention_out_plus_merge_is_bit_identical_to_attention_plus_merge(case,
         L[:3] = [0, 31, 32]
         inp = W.make_inputs(w, DEV, lengths=L)
         ctx = None
-    elif case == "groups":
-        tpg = 4
+    elif case in ("groups", "wide_groups"):
+        # 4 tokens x 8 heads: 32 head columns, two passes per wave; 16 tokens: 128 columns, a
+        # workgroup per worker (its own stores of records and final rows)
+        tpg = 4 if case == "groups" else 16
         rows = _grouped_rows(tpg)
         L = np.array([r[0] for r in rows], dtype=np.int32)
         slots = np.array([r[1] for r in rows], dtype=np.int32)
         live = np.array([r[2] for r in rows])
-        w = small("earlyg", len(rows), 16, 2, "f16", 94)              # 32 head columns: two passes
+        w = small("earlyg", len(rows), 16, 2, "f16", 94)
         inp = W.make_inputs(w, DEV, lengths=L, n_slots=int(slots.max()) + 1, capacity=704, slots=slots)
         ctx = np.where(live, L + 1, 0).astype(np.int32)
+    elif case == "many_heads":
+        w = small("earlyh", 40, 72, 1, "bf16", 96)                    # five passes on one kv head
+        L = np.random.default_rng(6).integers(0, 500, size=40).astype(np.int32)
+        inp = W.make_inputs(w, DEV, lengths=L)
+        ctx = None
     else:
         w = W.Workload("earlyl", 1500, 8, 2, 128, "bf16", ("uniform", 0, 300), 95)   # many short strips
         inp = W.make_inputs(w, DEV)
