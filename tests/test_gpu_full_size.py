@@ -194,3 +194,52 @@ def test_whole_output_on_head_blocked_paged_slots(name):
             row = view[n // page_rows, n % page_rows]          # [H_kv, d] of the appended row
             assert torch.equal(row.view(torch.int16), new[b].view(torch.int16)), (which, b)
     pool.close()
+
+
+@pytest.mark.parametrize("name,T", [("c4", 16), ("c3", 16), ("c4", 4)])
+def test_whole_output_of_prefill_chunks_at_full_size(name, T):
+    """The workload's batch as B/T prefill chunks of T tokens, declared as token groups: chunks of 16
+    at C4 shape are 128 head columns per kv head (a workgroup per worker, two passes per wave), at
+    C3 shape 64 (one pass per wave), chunks of 4 at C4 shape 32 (two passes per wave).  Every entry
+    against the oracle, which appends the whole batch and then lets entry t attend rows [0, pos_t]
+    of its slot; the caches against the oracle's mirror, prompt by prompt."""
+    base = W.WORKLOADS[name]
+    prompts = base.batch // T
+    lengths0 = W.draw_lengths(base)[:prompts]
+    lengths = (np.repeat(lengths0, T) + np.tile(np.arange(T), prompts)).astype(np.int32)
+    slots = np.repeat(np.arange(prompts), T).astype(np.int32)
+    inp = W.make_inputs(base, DEV, lengths=lengths, slots=slots, n_slots=prompts)
+    w = inp["workload"]
+    k_pre, v_pre = inp["k_cache"].clone(), inp["v_cache"].clone()
+    p = G.problem_from_inputs(inp, tokens_per_group=T)
+    plan = G.gh_decode_split_plan(p)
+    assert plan.waves_per_worker == (1 if T == 4 else 4)
+    ws = G.alloc_workspace(p, DEV)
+    ws.fill_(float("nan"))
+    out = torch.full((w.batch, w.n_q_heads, w.head_dim), float("nan"), dtype=torch.float32,
+                     device=DEV)
+    G.decode_step(p, inp, ws, out)
+    torch.cuda.synchronize()
+    got = out.cpu().numpy().astype(np.float64)
+    # the oracle, a few prompts at a time: each prompt's slot once, its T entries on it
+    want = np.empty_like(got)
+    per = max(1, 64 // T)
+    for a in range(0, prompts, per):
+        b = min(prompts, a + per)
+        S, E = b - a, (b - a) * T
+        rows = slice(a * T, b * T)
+        sl = torch.arange(a, b, device=DEV)
+        kc, vc = W.bits(k_pre.index_select(0, sl)), W.bits(v_pre.index_select(0, sl))
+        strides = W.cache_shape_and_strides(S, w.n_kv_heads, inp["capacity"], w.head_dim,
+                                            inp["layout"])[1]
+        po = O.make_problem(E, w.n_q_heads, w.n_kv_heads, w.head_dim, W.DTYPE_CODE[w.dtype], S,
+                            inp["capacity"], inp["scale"], strides)
+        sid = np.repeat(np.arange(S), T).astype(np.int32)
+        pos = lengths[rows]
+        assert O.kv_append(po, kc, vc, W.bits(inp["k_new"][rows]), W.bits(inp["v_new"][rows]), sid,
+                           pos) == 0
+        want[rows] = O.decode_attention(po, W.bits(inp["q"][rows]), kc, vc, sid, pos + 1)
+        assert np.array_equal(W.bits(inp["k_cache"].index_select(0, sl)), kc)
+        assert np.array_equal(W.bits(inp["v_cache"].index_select(0, sl)), vc)
+    _report(name, f"chunks of {T}", got, want, lengths)
+    Hh.assert_tight(got, want, f"{name} chunks of {T}")
