@@ -35,9 +35,14 @@ __global__ __launch_bounds__(256) void decode_reduce_kernel(const ReduceArgs a) 
   const float* l = a.ws_l + row * a.n_chunks;
   const float* o = a.ws_o + row * a.n_chunks * kHeadDim + 2 * lane;
 
-  // The first two records are fetched before the count is known: they exist in the layout whatever
-  // the count says, most heads use one or two, and the count, the headers and the rows then cost
-  // one memory round trip instead of three.  What a record beyond the count holds is never used.
+  // A row that the attention kernel has stored already needs nothing: the count says so, and is
+  // read first (on batches where most rows are such, fetching records ahead of it was a third of
+  // this kernel's time: 16.8 -> 12.1 us on 65 536 rows of which three in four were done).
+  int used = a.ws_n[row];
+  if (used < 0) return;
+  // The first two records are fetched before the count is looked at further: they exist in the
+  // layout whatever it says, most heads use one or two, and the headers and the rows then cost one
+  // more memory round trip instead of two.  What a record beyond the count holds is never used.
   const bool two = a.n_chunks > 1;
   const float2 o0 = *reinterpret_cast<const float2*>(o);
   const float2 o1 = two ? *reinterpret_cast<const float2*>(o + kHeadDim) : make_float2(0.f, 0.f);
@@ -46,8 +51,6 @@ __global__ __launch_bounds__(256) void decode_reduce_kernel(const ReduceArgs a) 
   // ... and so are the headers of the first 64 records, one per lane, for heads with more
   const int ch = lane < a.n_chunks ? lane : 0;
   const float mh = m[ch], lh = l[ch];
-  int used = a.ws_n[row];
-  if (used < 0) return;                        // the attention kernel has stored this row already
   used = used < a.n_chunks ? used : a.n_chunks;
 
   float2 acc = make_float2(0.f, 0.f);
