@@ -821,7 +821,7 @@ struct TileCursor {
 //       together in LDS and read their operands from there.
 // FUSED: the whole step in one launch (see AttnArgs): append, attention and merge.
 template <bool BF16, bool GROUPED, int P, int COOP, bool FUSED>
-__global__ __launch_bounds__(COOP ? 64 * COOP : 256, COOP || P == 1 ? 2 : 1)
+__global__ __launch_bounds__(COOP ? 64 * COOP : 256, COOP ? 2 : 1)
 void attn_mfma_balanced_kernel(const AttnArgs a) {
   static_assert(!(FUSED && GROUPED), "the one-launch step is for batches of one token per slot");
   static_assert(!(FUSED && COOP), "the one-launch step runs a wave per worker");

@@ -130,7 +130,9 @@ struct Plan {
                             // this many groups, each split on its own)
 };
 
-constexpr int kBalancedWavesPerCU = 8;      // resident waves of the MFMA kernel per compute unit
+constexpr int kBalancedWavesPerCU = 4;      // waves of the balanced kernel per compute unit: one per
+                                            // SIMD (measured against two: 0.2-2% faster on the large
+                                            // workloads, 6-13% on batches of 16 to 64 sequences)
 constexpr int kBalancedMaxRecords = 64;     // partial records per (sequence, head)
 
 inline Plan make_plan(const gh_problem* p) {
@@ -145,7 +147,7 @@ inline Plan make_plan(const gh_problem* p) {
   const int all_groups = p->batch / tokens_per_group(p);
   const int groups = all_groups < kBalancedMaxBatch ? all_groups : kBalancedMaxBatch;   // of one launch
   // Head columns per kv head (a head group, or a token group's heads) in passes of 16:
-  //   up to 16: a wave carries one pass, two waves per SIMD;
+  //   up to 16: a wave carries one pass;
   //   up to 32: a wave carries two passes through one stream of tiles, at one wave per SIMD (the
   //             second pass's operands and accumulators take the other wave's registers);
   //   more:     the four waves of a workgroup form one worker that streams the tiles once -- each
@@ -168,10 +170,8 @@ inline Plan make_plan(const gh_problem* p) {
     pl.n_pass = n_strip;
     pl.share = share;
     pl.launch_groups = groups > 0 ? groups : 1;
-    // workers: a wave each, as many as are resident (eight per compute unit with one pass, four
-    // with two); or a workgroup each, two per compute unit
-    pl.n_workers = share == 4 ? kComputeUnits * 2
-                              : kComputeUnits * (pps == 1 ? kBalancedWavesPerCU : kBalancedWavesPerCU / 2);
+    // workers: a wave each, one per SIMD; or a workgroup each, two per compute unit
+    pl.n_workers = share == 4 ? kComputeUnits * 2 : kComputeUnits * kBalancedWavesPerCU;
     int64_t c = (4 * (int64_t)pl.n_workers + strips - 1) / strips + 1;
     if (c < 2) c = 2;
     if (c > kBalancedMaxRecords) c = kBalancedMaxRecords;
