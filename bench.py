@@ -178,7 +178,8 @@ def time_default_step(name, steps, warmup, keep):
 
 
 def ceiling(args):
-    """Rate of the streaming-read probe: 2048 waves (the attention kernel's grid) over 8 GiB."""
+    """Rate of the streaming-read probe over 8 GiB: 2048 waves (two per SIMD), and reads only
+    with 1024 (one per SIMD, the attention kernel's grid)."""
     import torch
     from paper_2501_11779_amd import binding as G
 
@@ -188,14 +189,14 @@ def ceiling(args):
     sink = torch.zeros(1, dtype=torch.int32, device="cuda")
     tiles_per_wave = nbytes // (n_waves * 16384)
     rows = {}
-    cases = [("reads only", 0, 0)]
+    cases = [("reads only", 0, 0, n_waves), ("reads only, one wave per SIMD", 0, 0, n_waves // 2)]
     for every in (64, 16):           # a 4 KiB store per 1 MiB / 256 KiB read by a wave
         for name, pol in (("plain", G.GH_PROBE_STORE_PLAIN), ("non-temporal", G.GH_PROBE_STORE_NT),
                           ("write-through", G.GH_PROBE_STORE_WRITE_THROUGH)):
-            cases.append((f"4 KiB {name} store per {every} tiles", every, pol))
-    for label, every, pol in cases:
+            cases.append((f"4 KiB {name} store per {every} tiles", every, pol, n_waves))
+    for label, every, pol, waves in cases:
         def run():
-            G.check(G.gh_probe_stream_read(src, nbytes, n_waves, every, pol, rec, sink))
+            G.check(G.gh_probe_stream_read(src, nbytes, waves, every, pol, rec, sink))
         for _ in range(args.warmup):
             run()
         ev = [torch.cuda.Event(enable_timing=True) for _ in range(2)]

@@ -188,7 +188,8 @@ def summarise_ceiling(args, work):
            "The rate the memory system gives the attention kernel's access shape when nothing else is "
            "in the way: 2048 waves, each reading its own contiguous share of 8 GiB in 16 KiB tiles of "
            "whole 128-byte lines, two tiles in flight, non-temporal loads; alone, and with a 4 KiB "
-           "store per wave every 64 or 16 tiles in each store policy.  A measurement aid; the "
+           "store per wave every 64 or 16 tiles in each store policy; reads alone also with 1024 waves, "
+           "one per SIMD.  A measurement aid; the "
            "roofline peak stays the published 8 TB/s.\n",
            "Written by `python -m paper_2501_11779_amd.rocprof_summary --ceiling`, which ran (from "
            "/tmp, `TMPDIR=/tmp`, `$R` = repository root):\n", "```", cmd, "```\n",
@@ -202,7 +203,7 @@ def summarise_ceiling(args, work):
             label = re.search(r"probe_stream_kernel<[^>]*>", r["Name"]).group(0)
             out.append(f"| `{label}` | {r['Calls']} | {avg / 1e3:.2f} | "
                        f"{float(r['MinNs']) / 1e3:.2f} | {rate:.0f} | {rate / 80:.1f} |")
-    out.append("\n(`<-1>`: no stores; `<0>` plain, `<1>` non-temporal, `<2>` write-through stores, the "
+    out.append("\n(`<-1>`: no stores, the average taken over the runs with 2048 and with 1024 waves; `<0>` plain, `<1>` non-temporal, `<2>` write-through stores, the "
                "average taken over both store spacings.)\n")
     out.append("bench.py's own HIP-event readings in the same run, per case:\n\n```")
     out += [ln for ln in log.splitlines() if ln.startswith("stream probe")]
