@@ -27,6 +27,8 @@ typedef enum { GH_PROBE_STORE_PLAIN = 0, GH_PROBE_STORE_NT = 1, GH_PROBE_STORE_W
  * 4 KiB to its own place in `rec` (device, n_waves * 4 KiB, 16-byte aligned) with
  * the given policy; 0: no stores and rec may be null.  sink: one device word
  * that keeps the loads alive (written only if the data XORs to a magic value).
+ * Waves run in workgroups of four; with n_waves <= 1024 every workgroup is placed
+ * on a compute unit of its own (one wave per SIMD; it reserves LDS it does not use).
  * Asynchronous on hip_stream.  Returns a gh_status (gh_tier2.h): GH_ERR_NULL,
  * GH_ERR_SHAPE for sizes that do not divide, GH_ERR_UNSUPPORTED for alignment
  * or an unknown policy, GH_ERR_HIP if the launch failed.

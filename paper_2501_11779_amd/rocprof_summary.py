@@ -187,7 +187,7 @@ def summarise_ceiling(args, work):
     out = ["# rocprofv3 summary: streaming-read probe (include/gh_probe.h), MI355X (gfx950)\n",
            "The rate the memory system gives the attention kernel's access shape when nothing else is "
            "in the way: 2048 waves, each reading its own contiguous share of 8 GiB in 16 KiB tiles of "
-           "whole 128-byte lines, two tiles in flight, non-temporal loads; alone, and with a 4 KiB "
+           "whole 128-byte lines, one to three tiles in flight, non-temporal loads; alone, and with a 4 KiB "
            "store per wave every 64 or 16 tiles in each store policy; reads alone also with 1024 waves, "
            "one per SIMD.  A measurement aid; the "
            "roofline peak stays the published 8 TB/s.\n",
