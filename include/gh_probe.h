@@ -23,7 +23,8 @@ typedef enum { GH_PROBE_STORE_PLAIN = 0, GH_PROBE_STORE_NT = 1, GH_PROBE_STORE_W
 /*
  * Streams `bytes` bytes at `src` (device, 16-byte aligned) once with n_waves
  * waves.  bytes must be a multiple of n_waves * 32 KiB and n_waves a multiple of
- * 4 in [4, 65536].  store_every > 0: after every store_every tiles a wave writes
+ * 4 in [4, 65536].  store_every > 0: after every store_every tiles (an odd number counts as
+ * the next even one) a wave writes
  * 4 KiB to its own place in `rec` (device, n_waves * 4 KiB, 16-byte aligned) with
  * the given policy; 0: no stores and rec may be null.  sink: one device word
  * that keeps the loads alive (written only if the data XORs to a magic value).

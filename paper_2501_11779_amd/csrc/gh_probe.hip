@@ -58,7 +58,8 @@ __global__ __launch_bounds__(256, 2) void probe_stream_kernel(const u32x4* src,
   // The loads of a tile are issued before the tile that arrived earlier is used: one to three
   // tiles in flight, never none.
   const uint32_t last = tiles_per_wave - 1;
-  // (store_every is even; 0 = no stores: one group holding every tile)
+  // (0 = no stores: one group holding every tile; tiles go in pairs, so an odd store_every acts as
+  // the next even number)
   const uint32_t group = POLICY >= 0 && store_every > 0 ? (uint32_t)store_every : tiles_per_wave;
   probe_load(ta, p);
   for (uint32_t t = 0; t < tiles_per_wave;) {
