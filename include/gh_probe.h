@@ -1,8 +1,8 @@
 /*
  * gh_probe.h -- measurement aid, not part of the method: a pure streaming read
  * of device memory in the access shape of the attention kernel (every wave walks
- * its own contiguous share in 16 KiB tiles of whole 128-byte lines, two tiles in
- * flight, non-temporal loads), optionally interleaved with record-sized stores.
+ * its own contiguous share in 16 KiB tiles of whole 128-byte lines, one to three
+ * tiles in flight, non-temporal loads), optionally interleaved with record-sized stores.
  * It gives the rate the memory system delivers to this access pattern when no
  * arithmetic, no strip border and no ragged tail is in the way -- the practical
  * ceiling the attention kernel's achieved bandwidth is read against (the
