@@ -827,7 +827,7 @@ void attn_mfma_balanced_kernel(const AttnArgs a) {
   static_assert(!(FUSED && COOP), "the one-launch step runs a wave per worker");
   constexpr int kThreads = COOP ? 64 * COOP : 256;
   extern __shared__ uint32_t lds[];
-  __shared__ uint32_t part[kThreads];
+  __shared__ uint32_t part[kThreads / 64];
   const int tid = threadIdx.x;
   const int B = a.batch;
   uint32_t* cum = lds;                                        // [B + 1]
@@ -868,15 +868,18 @@ void attn_mfma_balanced_kernel(const AttnArgs a) {
   const int lo = tid * per, hi = lo + per < B ? lo + per : B;
   uint32_t sum = 0;
   for (int b = lo; b < hi; ++b) sum += cum[b + 1];
-  part[tid] = sum;
-  __syncthreads();
-  for (int off = 1; off < kThreads; off <<= 1) {
-    const uint32_t add = tid >= off ? part[tid - off] : 0u;
-    __syncthreads();
-    part[tid] += add;
-    __syncthreads();
+  // prefix over the threads' sums: inside each wave by lane shuffles, across the waves through
+  // one LDS word per wave (one barrier instead of two per doubling step)
+  uint32_t upto = sum;                         // inclusive, within the wave
+#pragma unroll
+  for (int off = 1; off < 64; off <<= 1) {
+    const uint32_t below = __shfl_up(upto, off, 64);
+    if ((tid & 63) >= off) upto += below;
   }
-  uint32_t run = part[tid] - sum;              // exclusive prefix of this thread's segment
+  if ((tid & 63) == 63) part[tid >> 6] = upto;
+  __syncthreads();
+  uint32_t run = upto - sum;                   // exclusive prefix of this thread's segment
+  for (int w = 0; w < (tid >> 6); ++w) run += part[w];
   for (int b = lo; b < hi; ++b) {
     run += cum[b + 1];
     cum[b + 1] = run;
