@@ -113,6 +113,38 @@ def test_more_than_64_records_per_head(kernel):
     Hh.assert_parity(got, Hh.oracle_step(inp, host), "68 records")
 
 
+@pytest.mark.parametrize("route", ["three_kernels", "one_launch", "strips", "valu"])
+def test_one_very_long_context_in_a_small_batch(route):
+    """300 000 rows for one sequence (9 376 tiles per strip) beside two short ones: the balanced
+    split runs out of records per head (64), so its shares grow beyond an equal split (min_share)
+    and most waves get nothing; the strip kernel walks 2 344 tiles per wave; the vector kernel
+    merges its chunks 64 at a time."""
+    lengths = np.array([300000, 77, 4097], dtype=np.int32)
+    w = small("long", 3, 8, 2, "bf16", 57)
+    inp = W.make_inputs(w, DEV, lengths=lengths)
+    host = Hh.host_copy(inp)
+    want = Hh.oracle_step(inp, host)
+    if route in ("three_kernels", "valu"):
+        kernel = G.GH_KERNEL_MFMA if route == "three_kernels" else G.GH_KERNEL_VALU
+        got, p, _ = run_gpu(inp, 0, kernel)
+        if route == "three_kernels":
+            plan = G.gh_decode_split_plan(p)
+            assert plan.balanced and plan.n_chunks == 64
+            total = sum(-(-int(n + 1) // 32) for n in lengths) * w.n_kv_heads
+            assert plan.min_share > -(-total // plan.n_workers)      # the record bound binds
+    else:
+        p = G.problem_from_inputs(inp, kernel=G.GH_KERNEL_STRIPS if route == "strips" else G.GH_KERNEL_AUTO)
+        ws = G.alloc_step_workspace(p, DEV)
+        out = torch.full((w.batch, w.n_q_heads, 128), float("nan"), dtype=torch.float32, device=DEV)
+        G.decode_step_one_launch(p, inp, ws, out)
+        torch.cuda.synchronize()
+        got = out.cpu().numpy()
+    Hh.assert_parity(got, want, f"long context, {route}")
+    Hh.assert_tight(got, want, f"long context, {route}")
+    assert np.array_equal(W.bits(inp["k_cache"]), host["k_cache"])
+    assert np.array_equal(W.bits(inp["v_cache"]), host["v_cache"])
+
+
 def test_largest_batch_of_the_balanced_split():
     """4096 sequences: the per-sequence arrays fill the kernel's dynamic LDS to its limit."""
     B = 4096
